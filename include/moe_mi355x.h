@@ -1,0 +1,170 @@
+/*
+ * moe_mi355x.h -- C ABI of the single-GPU Mixture-of-Experts layer hot path for AMD MI355X (gfx950).
+ *
+ * One GPU's share of one MoE layer, forward and backward, as the FSMoE paper states the layer
+ * (Sec. 2.1): a gating function, an ordering function and its reverse, and E expert FFNs.
+ * Notation follows the paper's Table 1: N = B*L tokens, M embedding size, E experts, k top-k,
+ * f capacity factor, H expert hidden size, T capacity (maximum tokens per expert).
+ *
+ * Conventions that hold for every entry point
+ *   - Every tensor pointer is a DEVICE pointer to a dense row-major array owned by the caller.
+ *     The library never allocates, frees or keeps device memory and never synchronises: it
+ *     enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the default stream)
+ *     and returns.  Configuration structs and the size_t* outputs are HOST memory.
+ *   - Activations and weights have the element type cfg->dtype (fp32 or bf16 bit patterns).
+ *     Logits, probabilities, gate weights and their gradients are fp32.  Indices are int32.
+ *   - A, the number of kept (token, choice) assignments, is data dependent.  Buffers indexed by
+ *     expert rows are sized by the caller for N*k rows; kernels read A = offsets[E] on the device.
+ *     Rows at and beyond A are never read or written.
+ *   - Arguments are validated on the host before any launch.  A failed call launches nothing,
+ *     returns a status other than MOE_OK and leaves a message for moe_last_error().
+ *   - Device data are assumed finite.  Behaviour on NaN/Inf logits is unspecified.
+ *   - Calls that share output or workspace buffers must be ordered by the caller (same stream).
+ */
+#ifndef MOE_MI355X_H
+#define MOE_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = 1, /* NULL pointer, non-positive size, k > E, ... */
+  MOE_ERR_UNSUPPORTED = 2, /* a dtype / activation / size this build has no kernel for */
+  MOE_ERR_WORKSPACE = 3,   /* workspace or saved blob smaller than moe_workspace_bytes reports */
+  MOE_ERR_DEVICE = 4       /* the HIP runtime refused a launch */
+} moe_status_t;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
+
+/* Expert FFN types (Sec. 3.1 "Expert"): the two-layer GPT FFN with an element-wise activation,
+ * or the three-matrix Mixtral FFN (MOE_ACT_SWIGLU). */
+typedef enum { MOE_ACT_RELU = 0, MOE_ACT_GELU_TANH = 1, MOE_ACT_SWIGLU = 2, MOE_ACT_GELU_ERF = 3 } moe_act_t;
+
+typedef struct moe_config {
+  int32_t n_tokens;         /* N = B*L */
+  int32_t d_model;          /* M */
+  int32_t n_experts;        /* E, at most 256 */
+  int32_t d_hidden;         /* H */
+  int32_t top_k;            /* k, 1 <= k <= min(E, 8) */
+  int32_t capacity;         /* T, rows per expert; <= 0 means nothing is dropped (the paper's f = *) */
+  int32_t dtype;            /* moe_dtype_t of activations and weights */
+  int32_t act;              /* moe_act_t */
+  int32_t renormalize;      /* 1: G = Softmax(KeepTopK(H, k)) as printed in Sec. 2.1;
+                               0: softmax over all E, selected probabilities used as they are */
+  int32_t add_residual;     /* 1: y = x + MoE(x) (and dx += dy) */
+  int32_t accumulate_wgrad; /* 0: expert weight gradients are overwritten; 1: added to */
+} moe_config_t;
+
+/* T := k*f*N/E (Sec. 2.1, ordering function), evaluated as ((k*f)*N)/E in double and rounded up.
+ * Host function, no GPU work.  Returns -1 on non-positive arguments. */
+int32_t moe_capacity(int32_t n_tokens, int32_t n_experts, int32_t top_k, double f);
+
+/* Sizes in bytes of the scratch workspace every call below accepts (one size fits all calls
+ * with this cfg) and of the `saved` blob moe_layer_fwd fills for moe_layer_bwd.  Host function. */
+moe_status_t moe_workspace_bytes(const moe_config_t* cfg, size_t* workspace_bytes, size_t* saved_bytes);
+
+/* Gate + capacity (Sec. 2.1 "Gating Function" and the capacity rule of the ordering function).
+ *   logits[t,e] = fp32( sum_m x[t,m] * w_gate[m,e] + b_gate[e] ), the sum carried in fp64
+ *   topk_idx[t,j] = expert with the j-th largest logit (ties: lower index), j = 0 is the largest
+ *   probs = G(I): renormalize=1 -> softmax over the k kept logits, exactly 0 elsewhere;
+ *                 renormalize=0 -> softmax over all E
+ *   topk_w[t,j] = probs[t, topk_idx[t,j]]
+ *   pos[t,j]    = slot inside the expert: choices are served rank by rank (all j=0, then j=1, ...),
+ *                 tokens in order inside a rank, while the expert has fewer than T rows; else -1
+ *   count[e] = rows kept by expert e, offsets = exclusive prefix sum of count (offsets[E] = A)
+ *   row_of[t,j] = offsets[e] + pos[t,j] or -1;  src_of_row[row] = t*k + j  (entries >= A: -1)
+ * in : x [N,M] dtype, w_gate [M,E] dtype, b_gate [E] fp32 or NULL
+ * out: logits [N,E] f32, probs [N,E] f32, topk_idx [N,k] i32, topk_w [N,k] f32, pos [N,k] i32,
+ *      row_of [N,k] i32, count [E] i32, offsets [E+1] i32, src_of_row [N*k] i32
+ * workspace: moe_workspace_bytes. */
+moe_status_t moe_route(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
+                       float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos,
+                       int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Ordering function (Sec. 2.1): xe[row_of[t,j], :] = x[t, :] for every kept assignment.  The
+ * compact expert-major buffer xe [A,M] is the paper's (E,T,M) layout without its padding rows:
+ * expert e owns rows offsets[e] .. offsets[e+1]-1.  Pure copy, bit exact. */
+moe_status_t moe_dispatch(const moe_config_t* cfg, const void* x, const int32_t* row_of, void* xe, void* stream);
+
+/* Backward of the ordering function: dx[t,:] = sum over kept j of dxe[row_of[t,j], :]
+ * (+ dy[t,:] when cfg->add_residual; dy may be NULL otherwise).  dx is overwritten. */
+moe_status_t moe_dispatch_bwd(const moe_config_t* cfg, const void* dxe, const int32_t* row_of, const void* dy,
+                              void* dx, void* stream);
+
+/* Experts (Sec. 2.1 "Experts", Sec. 3.1 "Expert"): Q_e = e_e(rows of expert e) for every expert.
+ *   two-layer: a1 = xe.W1_e, hh = act(a1), q = hh.W2_e
+ *   Mixtral:   a1 = xe.W1_e, a3 = xe.W3_e, hh = silu(a1)*a3, q = hh.W2_e
+ * in : xe [A,M], offsets [E+1], w1 [E,M,H], w3 [E,M,H] (NULL unless SWIGLU), w2 [E,H,M]
+ * out: q [A,M]; stored activations for the backward pass (Sec. 4.4): a1 [A,H], a3 [A,H]
+ *      (NULL unless SWIGLU), hh [A,H]; all dtype, all sized for N*k rows.
+ * bf16 needs M and H to be multiples of 8 (16-byte rows). */
+moe_status_t moe_expert_ffn_fwd(const moe_config_t* cfg, const void* xe, const int32_t* offsets, const void* w1,
+                                const void* w3, const void* w2, void* q, void* a1, void* a3, void* hh,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of the experts (Sec. 4.4: gradients of input and of weights, twice the forward work).
+ *   dhh = dq.W2_e^T, dW2_e = hh^T.dq, da1/da3 through the activation, dxe = da1.W1_e^T (+ da3.W3_e^T),
+ *   dW1_e = xe^T.da1, dW3_e = xe^T.da3.  Experts with no rows get zero gradients (or are left
+ *   unchanged when cfg->accumulate_wgrad).
+ * out: dxe [A,M], dw1 [E,M,H], dw3 [E,M,H] (NULL unless SWIGLU), dw2 [E,H,M], all dtype. */
+moe_status_t moe_expert_ffn_bwd(const moe_config_t* cfg, const void* dq, const void* xe, const int32_t* offsets,
+                                const void* w1, const void* w3, const void* w2, const void* a1, const void* a3,
+                                const void* hh, void* dxe, void* dw1, void* dw3, void* dw2, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
+/* I-ordering function (Sec. 2.1): expert outputs go back to token order, scaled by the gate value:
+ * y[t,:] = sum over kept j of topk_w[t,j] * q[row_of[t,j], :]  (+ x[t,:] when cfg->add_residual).
+ * A token whose every choice was dropped gets 0 (or x[t,:]).  The sum is carried in fp32. */
+moe_status_t moe_combine(const moe_config_t* cfg, const void* q, const float* topk_w, const int32_t* row_of,
+                         const void* x, void* y, void* stream);
+
+/* Backward of the I-ordering: dq[row_of[t,j], :] = topk_w[t,j] * dy[t, :] and
+ * dtopk_w[t,j] = <dy[t,:], q[row_of[t,j],:]> (0 for dropped choices). */
+moe_status_t moe_combine_bwd(const moe_config_t* cfg, const void* dy, const void* q, const float* topk_w,
+                             const int32_t* row_of, void* dq, float* dtopk_w, void* stream);
+
+/* Backward of the gate with the routing decision held fixed: g[t,e] = dtopk_w[t,j] where
+ * e = topk_idx[t,j] and the choice was kept, else 0; dlogits = probs * (g - <g, probs>);
+ * dw_gate = x^T.dlogits, db_gate = column sums of dlogits, dx += dlogits.W_g^T.
+ * in : x [N,M], w_gate [M,E], probs [N,E] (as written by moe_route), topk_idx, pos, dtopk_w [N,k]
+ * out: dw_gate [M,E] dtype, db_gate [E] f32 or NULL, dx [N,M] dtype ACCUMULATED INTO (read-modify-write).
+ * workspace: moe_workspace_bytes. */
+moe_status_t moe_route_bwd(const moe_config_t* cfg, const void* x, const void* w_gate, const float* probs,
+                           const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                           float* db_gate, void* dx, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The whole layer forward: gate, ordering, experts, I-ordering in one call (Sec. 2.1, Fig. 1).
+ * out: y [N,M]; `saved` (saved_bytes from moe_workspace_bytes) keeps the routing and the stored
+ * activations for moe_layer_bwd. */
+moe_status_t moe_layer_fwd(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
+                           const void* w1, const void* w3, const void* w2, void* y, void* saved, size_t saved_bytes,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* The whole layer backward (Sec. 4.4) from the blob moe_layer_fwd left.
+ * out: dx [N,M] (overwritten), dw_gate [M,E], db_gate [E] f32 or NULL, dw1, dw3 (NULL unless SWIGLU), dw2. */
+moe_status_t moe_layer_bwd(const moe_config_t* cfg, const void* dy, const void* x, const void* w_gate,
+                           const void* w1, const void* w3, const void* w2, const void* saved, size_t saved_bytes,
+                           void* dx, void* dw_gate, float* db_gate, void* dw1, void* dw3, void* dw2,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Where inside `saved` a tensor lives (for inspection and tests).  Host function. */
+typedef enum {
+  MOE_SAVED_LOGITS = 0, MOE_SAVED_PROBS, MOE_SAVED_TOPK_IDX, MOE_SAVED_TOPK_W, MOE_SAVED_POS, MOE_SAVED_ROW_OF,
+  MOE_SAVED_COUNT, MOE_SAVED_OFFSETS, MOE_SAVED_SRC_OF_ROW, MOE_SAVED_XE, MOE_SAVED_A1, MOE_SAVED_A3,
+  MOE_SAVED_HH, MOE_SAVED_Q, MOE_SAVED_N_
+} moe_saved_tensor_t;
+moe_status_t moe_saved_offset(const moe_config_t* cfg, int32_t which, size_t* byte_offset, size_t* n_bytes);
+
+/* Message of the last failed call on this host thread ("" if none).  Static storage. */
+const char* moe_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_MI355X_H */

@@ -96,6 +96,16 @@ def gate_weights(logits, topk_idx, renormalize):
     return np.take_along_axis(p, topk_idx.astype(np.int64), axis=1)
 
 
+def gate_dense(logits, topk_idx, renormalize):
+    """G(I) as an [N,E] matrix: Softmax(KeepTopK(H, k)) (zeros off the top-k) when renormalize=1,
+    the softmax over all E otherwise."""
+    if not renormalize:
+        return softmax_all(logits)
+    g = np.zeros(np.shape(logits), np.float64)
+    np.put_along_axis(g, topk_idx.astype(np.int64), gate_weights(logits, topk_idx, 1), axis=1)
+    return g
+
+
 # ----------------------------------------------------------------------------- capacity and ordering
 
 def capacity(n_tokens, n_experts, top_k, f):
@@ -312,12 +322,7 @@ def gate_bwd(x, w_gate, logits, topk_idx, pos, dtopk_w, renormalize, has_bias):
         for j in range(k):
             if pos[t, j] >= 0:
                 g[t, topk_idx[t, j]] = dtopk_w[t, j]
-    if renormalize:
-        w = gate_weights(logits, topk_idx, 1)
-        p = np.zeros((n, e_cnt), np.float64)
-        np.put_along_axis(p, topk_idx.astype(np.int64), w, axis=1)
-    else:
-        p = softmax_all(logits)
+    p = gate_dense(logits, topk_idx, renormalize)
     dl = p * (g - (g * p).sum(axis=1, keepdims=True))
     dw_gate = x.T @ dl
     db_gate = dl.sum(axis=0) if has_bias else None
@@ -331,8 +336,8 @@ def route(x, w_gate, b_gate, k, cap, renormalize, logit_dtype=np.float32):
     idx = keep_top_k(logits, k)
     w = gate_weights(logits, idx, renormalize)
     pos, count, offsets, row_of, src_of_row = assign_positions(idx, w_gate.shape[1], cap)
-    return dict(logits=logits, probs=softmax_all(logits), topk_idx=idx, topk_w=w, pos=pos, count=count,
-                offsets=offsets, row_of=row_of, src_of_row=src_of_row)
+    return dict(logits=logits, probs=gate_dense(logits, idx, renormalize), topk_idx=idx, topk_w=w, pos=pos,
+                count=count, offsets=offsets, row_of=row_of, src_of_row=src_of_row)
 
 
 def layer_fwd(x, w_gate, b_gate, w1, w3, w2, k, cap, act, renormalize, add_residual, logit_dtype=np.float32):

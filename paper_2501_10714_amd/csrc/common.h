@@ -1,0 +1,129 @@
+// Internal helpers shared by the HIP sources of the MoE hot path (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/moe_mi355x.h"
+
+namespace moe {
+
+typedef uint16_t bf16_t;  // bf16 storage: the upper half of an fp32 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// round-to-nearest-even; inputs are finite by contract
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kVec = 4;  // elements per 16-byte access
+  __device__ static __forceinline__ float ld(const float* p) { return *p; }
+  __device__ static __forceinline__ void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int kVec = 8;
+  __device__ static __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+  __device__ static __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// 16-byte vector of elements, widened to fp32 lanes
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  float v[4];
+  __device__ __forceinline__ void load(const float* p) {
+    float4 r = *reinterpret_cast<const float4*>(p);
+    v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+  }
+  __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+};
+template <> struct Vec16<bf16_t> {
+  float v[8];
+  __device__ __forceinline__ void load(const bf16_t* p) {
+    uint4 r = *reinterpret_cast<const uint4*>(p);
+    uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+  }
+  __device__ __forceinline__ void store(bf16_t* p) const {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+// ----------------------------------------------------------------------------- activations (fp32)
+__device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + __expf(-z)); }
+__device__ __forceinline__ float siluf_(float z) { return z * sigmoidf_(z); }
+__device__ __forceinline__ float silu_gradf_(float z) {
+  float s = sigmoidf_(z);
+  return s * (1.0f + z * (1.0f - s));
+}
+__device__ __forceinline__ float act_fwd(float z, int act) {
+  if (act == MOE_ACT_RELU) return z > 0.0f ? z : 0.0f;
+  if (act == MOE_ACT_GELU_TANH) {
+    float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+    return 0.5f * z * (1.0f + tanhf(u));
+  }
+  return 0.5f * z * (1.0f + erff(z * 0.7071067811865476f));
+}
+__device__ __forceinline__ float act_grad(float z, int act) {
+  if (act == MOE_ACT_RELU) return z > 0.0f ? 1.0f : 0.0f;
+  if (act == MOE_ACT_GELU_TANH) {
+    float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+    float th = tanhf(u);
+    return 0.5f * (1.0f + th) + 0.5f * z * (1.0f - th * th) * 0.7978845608028654f * (1.0f + 0.134145f * z * z);
+  }
+  return 0.5f * (1.0f + erff(z * 0.7071067811865476f)) + z * __expf(-0.5f * z * z) * 0.3989422804014327f;
+}
+
+// ----------------------------------------------------------------------------- host side
+void set_error(const char* fmt, ...);
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+inline size_t elem_size(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
+
+#define MOE_CHECK_LAUNCH()                                                       \
+  do {                                                                           \
+    hipError_t e__ = hipGetLastError();                                          \
+    if (e__ != hipSuccess) {                                                     \
+      moe::set_error("%s:%d: launch failed: %s", __FILE__, __LINE__, hipGetErrorString(e__)); \
+      return MOE_ERR_DEVICE;                                                     \
+    }                                                                            \
+  } while (0)
+
+// ----------------------------------------------------------------------------- launchers (one per source file)
+// route.hip
+size_t route_workspace_bytes(const moe_config_t& c);
+moe_status_t launch_route(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
+                          float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
+                          int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s);
+size_t route_bwd_workspace_bytes(const moe_config_t& c);
+moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
+                              const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                              float* db_gate, void* dx, void* ws, hipStream_t s);
+// order.hip
+moe_status_t launch_dispatch(const moe_config_t& c, const void* x, const int32_t* row_of, void* xe, hipStream_t s);
+moe_status_t launch_dispatch_bwd(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* dy, void* dx,
+                                 hipStream_t s);
+moe_status_t launch_combine(const moe_config_t& c, const void* q, const float* topk_w, const int32_t* row_of,
+                            const void* x, void* y, hipStream_t s);
+moe_status_t launch_combine_bwd(const moe_config_t& c, const void* dy, const void* q, const float* topk_w,
+                                const int32_t* row_of, void* dq, float* dtopk_w, hipStream_t s);
+// expert_ffn.hip
+size_t expert_bwd_workspace_bytes(const moe_config_t& c);
+moe_status_t launch_expert_fwd(const moe_config_t& c, const void* xe, const int32_t* offsets, const void* w1,
+                               const void* w3, const void* w2, void* q, void* a1, void* a3, void* hh, hipStream_t s);
+moe_status_t launch_expert_bwd(const moe_config_t& c, const void* dq, const void* xe, const int32_t* offsets,
+                               const void* w1, const void* w3, const void* w2, const void* a1, const void* a3,
+                               const void* hh, void* dxe, void* dw1, void* dw3, void* dw2, void* ws, hipStream_t s);
+
+}  // namespace moe

@@ -1,0 +1,217 @@
+// Ordering and I-ordering functions of the MoE layer (FSMoE Sec. 2.1) and their backward passes.
+//
+// All four kernels are HBM-bound row movers.  They walk TOKENS, not expert rows: a token's row is
+// read once and fanned out to (or gathered from) its k expert rows, so the traffic is the
+// algorithmic minimum  N*M*b + A*M*b.  Rows move as 16-byte vectors; a row is covered by a group
+// of `tpr` consecutive lanes (a power of two), so one wave touches whole contiguous rows.
+#include "common.h"
+
+namespace moe {
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kMaxK = 8;
+
+struct RowMap {
+  int tpr;  // threads per row (power of two, <= kBlock)
+  int rpb;  // rows per block
+};
+
+inline RowMap row_map(int chunks_per_row) {
+  int tpr = 1;
+  while (tpr < chunks_per_row && tpr < kBlock) tpr <<= 1;
+  return RowMap{tpr, kBlock / tpr};
+}
+
+// xe[row_of[t,j], :] = x[t, :]
+template <typename T>
+__global__ __launch_bounds__(kBlock) void dispatch_kernel(const T* __restrict__ x, const int32_t* __restrict__ row_of,
+                                                          T* __restrict__ xe, int n_tokens, int d_model, int top_k,
+                                                          int tpr) {
+  constexpr int V = Elem<T>::kVec;
+  const int rpb = kBlock / tpr;
+  const int t = blockIdx.x * rpb + threadIdx.x / tpr;
+  if (t >= n_tokens) return;
+  const int lane = threadIdx.x % tpr;
+  const int chunks = d_model / V;
+  int rows[kMaxK];
+#pragma unroll
+  for (int j = 0; j < kMaxK; ++j) rows[j] = j < top_k ? row_of[(size_t)t * top_k + j] : -1;
+  const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)t * d_model);
+  for (int c = lane; c < chunks; c += tpr) {
+    uint4 v = src[c];
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j)
+      if (rows[j] >= 0) reinterpret_cast<uint4*>(xe + (size_t)rows[j] * d_model)[c] = v;
+  }
+}
+
+// out[t,:] = sum_j scale_j * src[row_of[t,j], :] (+ res[t,:]);  scale_j = w[t,j] or 1
+template <typename T, bool kWeighted>
+__global__ __launch_bounds__(kBlock) void gather_sum_kernel(const T* __restrict__ src, const float* __restrict__ w,
+                                                            const int32_t* __restrict__ row_of,
+                                                            const T* __restrict__ res, T* __restrict__ out,
+                                                            int n_tokens, int d_model, int top_k, int tpr) {
+  constexpr int V = Elem<T>::kVec;
+  const int rpb = kBlock / tpr;
+  const int t = blockIdx.x * rpb + threadIdx.x / tpr;
+  if (t >= n_tokens) return;
+  const int lane = threadIdx.x % tpr;
+  const int chunks = d_model / V;
+  int rows[kMaxK];
+  float sc[kMaxK];
+#pragma unroll
+  for (int j = 0; j < kMaxK; ++j) {
+    rows[j] = j < top_k ? row_of[(size_t)t * top_k + j] : -1;
+    sc[j] = (kWeighted && j < top_k) ? w[(size_t)t * top_k + j] : 1.0f;
+  }
+  for (int c = lane; c < chunks; c += tpr) {
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j) {
+      if (rows[j] >= 0) {
+        Vec16<T> v;
+        v.load(src + (size_t)rows[j] * d_model + c * V);
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = kWeighted ? fmaf(sc[j], v.v[i], acc[i]) : acc[i] + v.v[i];
+      }
+    }
+    if (res != nullptr) {
+      Vec16<T> r;
+      r.load(res + (size_t)t * d_model + c * V);
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc[i] += r.v[i];
+    }
+    Vec16<T> o;
+#pragma unroll
+    for (int i = 0; i < V; ++i) o.v[i] = acc[i];
+    o.store(out + (size_t)t * d_model + c * V);
+  }
+}
+
+// dq[row_of[t,j], :] = w[t,j] * dy[t, :];  dtopk_w[t,j] = <dy[t,:], q[row_of[t,j],:]>
+template <typename T>
+__global__ __launch_bounds__(kBlock) void combine_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ q,
+                                                             const float* __restrict__ w,
+                                                             const int32_t* __restrict__ row_of, T* __restrict__ dq,
+                                                             float* __restrict__ dtopk_w, int n_tokens, int d_model,
+                                                             int top_k, int tpr) {
+  constexpr int V = Elem<T>::kVec;
+  __shared__ float red[kMaxK][kBlock / 64];
+  const int rpb = kBlock / tpr;
+  const int t = blockIdx.x * rpb + threadIdx.x / tpr;
+  const bool live = t < n_tokens;
+  const int lane = threadIdx.x % tpr;
+  const int chunks = d_model / V;
+  int rows[kMaxK];
+  float sc[kMaxK], dot[kMaxK];
+#pragma unroll
+  for (int j = 0; j < kMaxK; ++j) {
+    rows[j] = (live && j < top_k) ? row_of[(size_t)t * top_k + j] : -1;
+    sc[j] = (live && j < top_k) ? w[(size_t)t * top_k + j] : 0.0f;
+    dot[j] = 0.0f;
+  }
+  if (live) {
+    for (int c = lane; c < chunks; c += tpr) {
+      Vec16<T> g;
+      g.load(dy + (size_t)t * d_model + c * V);
+#pragma unroll
+      for (int j = 0; j < kMaxK; ++j) {
+        if (rows[j] >= 0) {
+          Vec16<T> qv, o;
+          qv.load(q + (size_t)rows[j] * d_model + c * V);
+#pragma unroll
+          for (int i = 0; i < V; ++i) {
+            dot[j] = fmaf(g.v[i], qv.v[i], dot[j]);
+            o.v[i] = sc[j] * g.v[i];
+          }
+          o.store(dq + (size_t)rows[j] * d_model + c * V);
+        }
+      }
+    }
+  }
+  // reduce the partial dots over the tpr lanes of the row: butterflies inside a wave, LDS across waves
+  const int in_wave = tpr < 64 ? tpr : 64;
+#pragma unroll
+  for (int j = 0; j < kMaxK; ++j) {
+    if (j < top_k) {
+      float v = dot[j];
+      for (int o = in_wave >> 1; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+      dot[j] = v;
+    }
+  }
+  if (tpr > 64) {  // tpr == kBlock: the whole block serves one token
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0)
+      for (int j = 0; j < top_k; ++j) red[j][wave] = dot[j];
+    __syncthreads();
+    if (threadIdx.x < top_k && live) {
+      float v = 0.0f;
+      for (int wv = 0; wv < kBlock / 64; ++wv) v += red[threadIdx.x][wv];
+      dtopk_w[(size_t)t * top_k + threadIdx.x] = v;  // dropped choices never accumulated: 0
+    }
+  } else if (live && lane == 0) {
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j)
+      if (j < top_k) dtopk_w[(size_t)t * top_k + j] = dot[j];
+  }
+}
+
+template <typename T>
+moe_status_t dispatch_t(const moe_config_t& c, const void* x, const int32_t* row_of, void* xe, hipStream_t s) {
+  RowMap m = row_map(c.d_model / Elem<T>::kVec);
+  hipLaunchKernelGGL(dispatch_kernel<T>, dim3(ceil_div(c.n_tokens, m.rpb)), dim3(kBlock), 0, s, (const T*)x, row_of,
+                     (T*)xe, c.n_tokens, c.d_model, c.top_k, m.tpr);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
+}
+
+template <typename T, bool kWeighted>
+moe_status_t gather_t(const moe_config_t& c, const void* src, const float* w, const int32_t* row_of, const void* res,
+                      void* out, hipStream_t s) {
+  RowMap m = row_map(c.d_model / Elem<T>::kVec);
+  hipLaunchKernelGGL((gather_sum_kernel<T, kWeighted>), dim3(ceil_div(c.n_tokens, m.rpb)), dim3(kBlock), 0, s,
+                     (const T*)src, w, row_of, (const T*)res, (T*)out, c.n_tokens, c.d_model, c.top_k, m.tpr);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
+}
+
+template <typename T>
+moe_status_t combine_bwd_t(const moe_config_t& c, const void* dy, const void* q, const float* w, const int32_t* row_of,
+                           void* dq, float* dtopk_w, hipStream_t s) {
+  RowMap m = row_map(c.d_model / Elem<T>::kVec);
+  hipLaunchKernelGGL(combine_bwd_kernel<T>, dim3(ceil_div(c.n_tokens, m.rpb)), dim3(kBlock), 0, s, (const T*)dy,
+                     (const T*)q, w, row_of, (T*)dq, dtopk_w, c.n_tokens, c.d_model, c.top_k, m.tpr);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
+}
+
+}  // namespace
+
+moe_status_t launch_dispatch(const moe_config_t& c, const void* x, const int32_t* row_of, void* xe, hipStream_t s) {
+  return c.dtype == MOE_BF16 ? dispatch_t<bf16_t>(c, x, row_of, xe, s) : dispatch_t<float>(c, x, row_of, xe, s);
+}
+
+moe_status_t launch_dispatch_bwd(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* dy, void* dx,
+                                 hipStream_t s) {
+  const void* res = c.add_residual ? dy : nullptr;
+  return c.dtype == MOE_BF16 ? gather_t<bf16_t, false>(c, dxe, nullptr, row_of, res, dx, s)
+                             : gather_t<float, false>(c, dxe, nullptr, row_of, res, dx, s);
+}
+
+moe_status_t launch_combine(const moe_config_t& c, const void* q, const float* topk_w, const int32_t* row_of,
+                            const void* x, void* y, hipStream_t s) {
+  const void* res = c.add_residual ? x : nullptr;
+  return c.dtype == MOE_BF16 ? gather_t<bf16_t, true>(c, q, topk_w, row_of, res, y, s)
+                             : gather_t<float, true>(c, q, topk_w, row_of, res, y, s);
+}
+
+moe_status_t launch_combine_bwd(const moe_config_t& c, const void* dy, const void* q, const float* topk_w,
+                                const int32_t* row_of, void* dq, float* dtopk_w, hipStream_t s) {
+  return c.dtype == MOE_BF16 ? combine_bwd_t<bf16_t>(c, dy, q, topk_w, row_of, dq, dtopk_w, s)
+                             : combine_bwd_t<float>(c, dy, q, topk_w, row_of, dq, dtopk_w, s);
+}
+
+}  // namespace moe

@@ -1,0 +1,583 @@
+// Gate, top-k, capacity positions (FSMoE Sec. 2.1 "Gating Function" and the capacity rule of the
+// ordering function) and the gate's backward pass (Sec. 4.4).
+//
+// Forward, five launches on one stream:
+//   1. widen_gate_kernel   W_g -> fp64, zero padded to [Mpad][EP]          (tiny)
+//   2. gate_topk_kernel    logits (fp64 accumulate, one rounding to fp32), top-k, G(I), and a
+//                          histogram of choices per (expert, rank j, 64-token tile)
+//   3. scan_hist_kernel    exclusive prefix over (j, tile) for every expert: the number of earlier
+//                          assignments to that expert in rank-major, token-minor order
+//   4. finalize_kernel     count = min(total, T), offsets = exclusive prefix of count
+//   5. positions_kernel    pos / row_of / src_of_row: tile base + rank among the wave's lanes
+// Positions come from prefix sums only (no atomics decide an index), so the result is the same on
+// every run and equals the serial walk "for j, for t".
+//
+// The logits kernel keeps one token per lane and splits K = d_model over the block's eight waves,
+// so the W_g row a wave needs is the same for all its lanes: it is read through scalar loads from
+// the fp64 copy and feeds v_fma_f64 as a scalar operand.  x goes through LDS (coalesced 16-byte
+// global loads, row reads by the owning lane).
+#include "common.h"
+
+namespace moe {
+namespace {
+
+constexpr int kTile = 64;          // tokens per block (one per lane)
+constexpr int kGateThreads = 512;  // 8 waves split K
+constexpr int kWaves = kGateThreads / 64;
+constexpr int kRowBytes = 512;     // bytes of one token row staged per K chunk
+constexpr int kRowStride = kRowBytes + 16;
+constexpr int kMaxK = 8;
+
+struct RoutePlan {
+  int ee;      // experts per register chunk (8,16,32,64)
+  int ep;      // padded expert count (multiple of ee)
+  int kce;     // elements per K chunk
+  int nkc;     // K chunks
+  int mpad;    // padded rows of the fp64 gate matrix
+  int nb;      // 64-token tiles
+  size_t off_wd, off_hist, off_total, bytes;
+};
+
+RoutePlan route_plan(const moe_config_t& c) {
+  RoutePlan p;
+  int e = c.n_experts;
+  p.ee = e <= 8 ? 8 : e <= 16 ? 16 : e <= 32 ? 32 : 64;
+  p.ep = ceil_div(e, p.ee) * p.ee;
+  p.kce = kRowBytes / (int)elem_size(c.dtype);
+  p.nkc = ceil_div(c.d_model, p.kce);
+  p.mpad = p.nkc * p.kce;
+  p.nb = ceil_div(c.n_tokens, kTile);
+  size_t o = 0;
+  p.off_wd = o; o += align_up((size_t)p.mpad * p.ep * sizeof(double), 256);
+  p.off_hist = o; o += align_up((size_t)e * c.top_k * p.nb * sizeof(int32_t), 256);
+  p.off_total = o; o += align_up((size_t)e * sizeof(int32_t), 256);
+  p.bytes = o;
+  return p;
+}
+
+template <typename T>
+__global__ void widen_gate_kernel(const T* __restrict__ w_gate, double* __restrict__ wd, int d_model, int n_experts,
+                                  int mpad, int ep) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= mpad * ep) return;
+  int m = i / ep, e = i % ep;
+  wd[i] = (m < d_model && e < n_experts) ? (double)Elem<T>::ld(w_gate + (size_t)m * n_experts + e) : 0.0;
+}
+
+template <typename T> struct Widen;
+template <> struct Widen<bf16_t> {
+  static constexpr int kN = 8;
+  __device__ static __forceinline__ void run(const uint4& r, double* d) {
+    uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      d[2 * i] = (double)__uint_as_float(w[i] << 16);
+      d[2 * i + 1] = (double)__uint_as_float(w[i] & 0xFFFF0000u);
+    }
+  }
+};
+template <> struct Widen<float> {
+  static constexpr int kN = 4;
+  __device__ static __forceinline__ void run(const uint4& r, double* d) {
+    d[0] = (double)__uint_as_float(r.x); d[1] = (double)__uint_as_float(r.y);
+    d[2] = (double)__uint_as_float(r.z); d[3] = (double)__uint_as_float(r.w);
+  }
+};
+
+template <typename T, int EE>
+__global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
+    const T* __restrict__ x, const double* __restrict__ wd, const float* __restrict__ b_gate,
+    float* __restrict__ logits, float* __restrict__ probs, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    int32_t* __restrict__ hist, int n_tokens, int d_model, int n_experts, int top_k, int renormalize, int ep, int nkc,
+    int nb) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* xs = smem;                                       // [kTile][kRowStride]
+  double* red = reinterpret_cast<double*>(smem + kTile * kRowStride);  // [EE][kTile]
+  float* lg = reinterpret_cast<float*>(red + EE * kTile);         // [kTile][n_experts + 1]
+  int32_t* hcnt = reinterpret_cast<int32_t*>(lg + kTile * (n_experts + 1));  // [top_k][n_experts]
+
+  constexpr int V = Widen<T>::kN;
+  constexpr int KCE = kRowBytes / (int)sizeof(T);
+  constexpr int kLoads = kTile * kRowBytes / 16 / kGateThreads;  // 16-byte loads per thread per chunk (4)
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int t0 = blockIdx.x * kTile;
+  const int lgs = n_experts + 1;
+
+  for (int i = tid; i < top_k * n_experts; i += kGateThreads) hcnt[i] = 0;
+
+  for (int ec = 0; ec < ep; ec += EE) {
+    double acc[EE];
+#pragma unroll
+    for (int e = 0; e < EE; ++e) acc[e] = 0.0;
+
+    uint4 pre[kLoads];
+    auto fetch = [&](int kc) {
+#pragma unroll
+      for (int r = 0; r < kLoads; ++r) {
+        int idx = tid + kGateThreads * r;
+        int row = idx / (kRowBytes / 16), c16 = idx % (kRowBytes / 16);
+        int t = t0 + row, k = kc * KCE + c16 * V;
+        pre[r] = (t < n_tokens && k < d_model) ? *reinterpret_cast<const uint4*>(x + (size_t)t * d_model + k)
+                                               : make_uint4(0, 0, 0, 0);
+      }
+    };
+    fetch(0);
+    for (int kc = 0; kc < nkc; ++kc) {
+      __syncthreads();  // previous chunk fully consumed
+#pragma unroll
+      for (int r = 0; r < kLoads; ++r) {
+        int idx = tid + kGateThreads * r;
+        int row = idx / (kRowBytes / 16), c16 = idx % (kRowBytes / 16);
+        *reinterpret_cast<uint4*>(xs + row * kRowStride + c16 * 16) = pre[r];
+      }
+      __syncthreads();
+      if (kc + 1 < nkc) fetch(kc + 1);
+      // this wave's share of the chunk: bytes [wave*64, wave*64+64) of every row
+      const unsigned char* my = xs + lane * kRowStride + wave * (kRowBytes / kWaves);
+      const int kw = kc * KCE + wave * (KCE / kWaves);
+#pragma unroll
+      for (int c = 0; c < kRowBytes / kWaves / 16; ++c) {
+        uint4 r = *reinterpret_cast<const uint4*>(my + c * 16);
+        double xd[V];
+        Widen<T>::run(r, xd);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          const double* __restrict__ wr = wd + (size_t)(kw + c * V + i) * ep + ec;  // wave-uniform address
+#pragma unroll
+          for (int e = 0; e < EE; ++e) acc[e] = fma(xd[i], wr[e], acc[e]);
+        }
+      }
+    }
+    // sum the eight K slices in wave order
+    for (int w = 0; w < kWaves; ++w) {
+      __syncthreads();
+      if (wave == w) {
+#pragma unroll
+        for (int e = 0; e < EE; ++e) red[e * kTile + lane] = (w == 0 ? 0.0 : red[e * kTile + lane]) + acc[e];
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < EE * kTile; i += kGateThreads) {
+      int e = i / kTile, tk = i % kTile;
+      if (ec + e < n_experts) {
+        double v = red[e * kTile + tk];
+        if (b_gate != nullptr) v += (double)b_gate[ec + e];
+        lg[tk * lgs + ec + e] = (float)v;
+      }
+    }
+    __syncthreads();
+  }
+
+  // logits out, coalesced over the tile
+  for (int i = tid; i < kTile * n_experts; i += kGateThreads) {
+    int tk = i / n_experts, e = i % n_experts;
+    if (t0 + tk < n_tokens) logits[(size_t)(t0 + tk) * n_experts + e] = lg[tk * lgs + e];
+  }
+
+  // top-k and G(I): one token per lane of wave 0
+  if (wave == 0) {
+    const int t = t0 + lane;
+    if (t < n_tokens) {
+      float* l = lg + lane * lgs;
+      int sel[kMaxK];
+      float selv[kMaxK];
+      float prev_v = 0.0f;
+      int prev_e = -1;
+      for (int j = 0; j < top_k; ++j) {
+        float bv = 0.0f;
+        int be = -1;
+        for (int e = 0; e < n_experts; ++e) {
+          float v = l[e];
+          bool eligible = (j == 0) || (v < prev_v) || (v == prev_v && e > prev_e);
+          if (eligible && (be < 0 || v > bv)) { bv = v; be = e; }
+        }
+        sel[j] = be; selv[j] = bv; prev_v = bv; prev_e = be;
+        topk_idx[(size_t)t * top_k + j] = be;
+        atomicAdd(&hcnt[j * n_experts + be], 1);
+      }
+      const float mx = selv[0];
+      if (renormalize) {
+        float z[kMaxK], s = 0.0f;
+        for (int j = 0; j < top_k; ++j) { z[j] = expf(selv[j] - mx); s += z[j]; }
+        for (int e = 0; e < n_experts; ++e) l[e] = 0.0f;
+        for (int j = 0; j < top_k; ++j) {
+          float w = z[j] / s;
+          l[sel[j]] = w;
+          topk_w[(size_t)t * top_k + j] = w;
+        }
+      } else {
+        float s = 0.0f;
+        for (int e = 0; e < n_experts; ++e) { float z = expf(l[e] - mx); l[e] = z; s += z; }
+        for (int e = 0; e < n_experts; ++e) l[e] = l[e] / s;
+        for (int j = 0; j < top_k; ++j) topk_w[(size_t)t * top_k + j] = l[sel[j]];
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < kTile * n_experts; i += kGateThreads) {
+    int tk = i / n_experts, e = i % n_experts;
+    if (t0 + tk < n_tokens) probs[(size_t)(t0 + tk) * n_experts + e] = lg[tk * lgs + e];
+  }
+  for (int i = tid; i < top_k * n_experts; i += kGateThreads) {
+    int j = i / n_experts, e = i % n_experts;
+    hist[((size_t)e * top_k + j) * nb + blockIdx.x] = hcnt[i];
+  }
+}
+
+// One block per expert: in-place exclusive prefix over its (rank j, tile) histogram entries.
+__global__ __launch_bounds__(256) void scan_hist_kernel(int32_t* __restrict__ hist, int32_t* __restrict__ total,
+                                                        int len) {
+  __shared__ int32_t part[256];
+  int32_t* h = hist + (size_t)blockIdx.x * len;
+  const int seg = (len + 255) / 256;
+  const int lo = threadIdx.x * seg, hi = min(lo + seg, len);
+  int32_t s = 0;
+  for (int i = lo; i < hi; ++i) s += h[i];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {  // Hillis-Steele inclusive scan
+    int32_t v = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+    __syncthreads();
+    part[threadIdx.x] += v;
+    __syncthreads();
+  }
+  int32_t run = part[threadIdx.x] - s;
+  for (int i = lo; i < hi; ++i) {
+    int32_t v = h[i];
+    h[i] = run;
+    run += v;
+  }
+  if (threadIdx.x == 255) total[blockIdx.x] = part[255];
+}
+
+__global__ void finalize_kernel(const int32_t* __restrict__ total, int32_t* __restrict__ count,
+                                int32_t* __restrict__ offsets, int n_experts, int capacity) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    int32_t run = 0;
+    for (int e = 0; e < n_experts; ++e) {
+      int32_t c = total[e];
+      if (capacity > 0 && c > capacity) c = capacity;
+      count[e] = c;
+      offsets[e] = run;
+      run += c;
+    }
+    offsets[n_experts] = run;
+  }
+}
+
+// One wave per 64-token tile, one token per lane.
+__global__ __launch_bounds__(256) void positions_kernel(const int32_t* __restrict__ topk_idx,
+                                                        const int32_t* __restrict__ base,
+                                                        const int32_t* __restrict__ offsets, int32_t* __restrict__ pos,
+                                                        int32_t* __restrict__ row_of, int32_t* __restrict__ src_of_row,
+                                                        int n_tokens, int n_experts, int top_k, int capacity, int nb) {
+  const int lane = threadIdx.x & 63;
+  const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int t = tile * kTile + lane;
+  const bool live = tile < nb && t < n_tokens;
+  if (tile < nb) {
+    for (int j = 0; j < top_k; ++j) {
+      const int e = live ? topk_idx[(size_t)t * top_k + j] : -1;
+      // rank among the lanes of this wave that chose the same expert and come earlier
+      int local = 0;
+      unsigned long long todo = __ballot(live);
+      while (todo != 0ull) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int e0 = __shfl(e, leader, 64);
+        const unsigned long long same = __ballot(live && e == e0);
+        if (live && e == e0) local = __popcll(same & ((1ull << lane) - 1ull));
+        todo &= ~same;
+      }
+      if (live) {
+        const int rank = base[((size_t)e * top_k + j) * nb + tile] + local;
+        const bool kept = capacity <= 0 || rank < capacity;
+        const int p = kept ? rank : -1;
+        const int row = kept ? offsets[e] + rank : -1;
+        pos[(size_t)t * top_k + j] = p;
+        row_of[(size_t)t * top_k + j] = row;
+        if (kept) src_of_row[row] = t * top_k + j;
+      }
+    }
+  }
+  // rows past A have no source
+  const int a = offsets[n_experts];
+  const int total = n_tokens * top_k;
+  for (int r = a + blockIdx.x * blockDim.x + threadIdx.x; r < total; r += gridDim.x * blockDim.x) src_of_row[r] = -1;
+}
+
+template <typename T, int EE>
+void launch_gate(const moe_config_t& c, const RoutePlan& p, const void* x, const double* wd, const float* b_gate,
+                 float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* hist, hipStream_t s) {
+  size_t lds = (size_t)kTile * kRowStride + (size_t)EE * kTile * sizeof(double) +
+               (size_t)kTile * (c.n_experts + 1) * sizeof(float) + (size_t)c.top_k * c.n_experts * sizeof(int32_t);
+  static bool attr_set = false;  // LDS above 64 KB must be requested once per kernel
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gate_topk_kernel<T, EE>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gate_topk_kernel<T, EE>), dim3(p.nb), dim3(kGateThreads), lds, s, (const T*)x, wd, b_gate, logits,
+                     probs, topk_idx, topk_w, hist, c.n_tokens, c.d_model, c.n_experts, c.top_k, c.renormalize, p.ep,
+                     p.nkc, p.nb);
+}
+
+template <typename T>
+moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
+                     float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
+                     int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
+  RoutePlan p = route_plan(c);
+  unsigned char* w = static_cast<unsigned char*>(ws);
+  double* wd = reinterpret_cast<double*>(w + p.off_wd);
+  int32_t* hist = reinterpret_cast<int32_t*>(w + p.off_hist);
+  int32_t* total = reinterpret_cast<int32_t*>(w + p.off_total);
+  int nwd = p.mpad * p.ep;
+  hipLaunchKernelGGL(widen_gate_kernel<T>, dim3(ceil_div(nwd, 256)), dim3(256), 0, s, (const T*)w_gate, wd, c.d_model,
+                     c.n_experts, p.mpad, p.ep);
+  MOE_CHECK_LAUNCH();
+  switch (p.ee) {
+    case 8: launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
+    case 16: launch_gate<T, 16>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
+    case 32: launch_gate<T, 32>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
+    default: launch_gate<T, 64>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
+  }
+  MOE_CHECK_LAUNCH();
+  hipLaunchKernelGGL(scan_hist_kernel, dim3(c.n_experts), dim3(256), 0, s, hist, total, c.top_k * p.nb);
+  MOE_CHECK_LAUNCH();
+  hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(64), 0, s, total, count, offsets, c.n_experts, c.capacity);
+  MOE_CHECK_LAUNCH();
+  hipLaunchKernelGGL(positions_kernel, dim3(ceil_div(p.nb, 4)), dim3(256), 0, s, topk_idx, hist, offsets, pos, row_of,
+                     src_of_row, c.n_tokens, c.n_experts, c.top_k, c.capacity, p.nb);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
+}
+
+// ----------------------------------------------------------------------------- backward of the gate
+
+constexpr int kDwTokens = 256;   // tokens per partial-sum tile of dW_g
+constexpr int kDwThreads = 128;
+constexpr int kDxTokens = 16;    // tokens per block of the dx update
+constexpr int kEc = 8;           // experts per register chunk
+
+struct RouteBwdPlan {
+  int ntile;
+  size_t off_dl, off_part, off_bpart, bytes;
+};
+
+RouteBwdPlan route_bwd_plan(const moe_config_t& c) {
+  RouteBwdPlan p;
+  p.ntile = ceil_div(c.n_tokens, kDwTokens);
+  size_t o = 0;
+  p.off_dl = o; o += align_up((size_t)c.n_tokens * c.n_experts * sizeof(float), 256);
+  p.off_part = o; o += align_up((size_t)p.ntile * c.d_model * c.n_experts * sizeof(float), 256);
+  p.off_bpart = o; o += align_up((size_t)p.ntile * c.n_experts * sizeof(float), 256);
+  p.bytes = o;
+  return p;
+}
+
+// dlogits[t,e] = probs[t,e] * (g[t,e] - <g[t,:], probs[t,:]>), g = dtopk_w scattered to the kept choices
+__global__ __launch_bounds__(256) void dlogits_kernel(const float* __restrict__ probs,
+                                                      const int32_t* __restrict__ topk_idx,
+                                                      const int32_t* __restrict__ pos,
+                                                      const float* __restrict__ dtopk_w, float* __restrict__ dl,
+                                                      int n_tokens, int n_experts, int top_k) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)n_tokens * n_experts) return;
+  const int t = (int)(i / n_experts), e = (int)(i % n_experts);
+  float s = 0.0f, g = 0.0f;
+  for (int j = 0; j < top_k; ++j) {
+    const size_t a = (size_t)t * top_k + j;
+    if (pos[a] >= 0) {
+      const int ej = topk_idx[a];
+      const float d = dtopk_w[a];
+      s = fmaf(d, probs[(size_t)t * n_experts + ej], s);
+      if (ej == e) g = d;
+    }
+  }
+  dl[i] = probs[i] * (g - s);
+}
+
+// dx[t, m..m+V) += sum_e dl[t,e] * W_g[m.., e]; a thread owns one 16-byte column chunk for kDxTokens tokens
+template <typename T>
+__global__ __launch_bounds__(256) void gate_dx_kernel(const float* __restrict__ dl, const T* __restrict__ w_gate,
+                                                      T* __restrict__ dx, int n_tokens, int d_model, int n_experts) {
+  constexpr int V = Elem<T>::kVec;
+  extern __shared__ float dls[];  // [kDxTokens][n_experts]
+  const int t0 = blockIdx.x * kDxTokens;
+  for (int i = threadIdx.x; i < kDxTokens * n_experts; i += 256) {
+    int tk = i / n_experts;
+    dls[i] = (t0 + tk < n_tokens) ? dl[(size_t)t0 * n_experts + i] : 0.0f;
+  }
+  __syncthreads();
+  const int m = (blockIdx.y * 256 + threadIdx.x) * V;
+  if (m >= d_model) return;
+  float acc[kDxTokens][V];
+#pragma unroll
+  for (int tk = 0; tk < kDxTokens; ++tk)
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[tk][i] = 0.0f;
+  for (int ec = 0; ec < n_experts; ec += kEc) {
+    float w[V][kEc];
+#pragma unroll
+    for (int i = 0; i < V; ++i)
+#pragma unroll
+      for (int e = 0; e < kEc; ++e)
+        w[i][e] = (ec + e < n_experts) ? Elem<T>::ld(w_gate + (size_t)(m + i) * n_experts + ec + e) : 0.0f;
+#pragma unroll
+    for (int tk = 0; tk < kDxTokens; ++tk)
+#pragma unroll
+      for (int e = 0; e < kEc; ++e) {
+        const float d = (ec + e < n_experts) ? dls[tk * n_experts + ec + e] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[tk][i] = fmaf(d, w[i][e], acc[tk][i]);
+      }
+  }
+#pragma unroll
+  for (int tk = 0; tk < kDxTokens; ++tk) {
+    if (t0 + tk < n_tokens) {
+      Vec16<T> v;
+      T* p = dx + (size_t)(t0 + tk) * d_model + m;
+      v.load(p);
+#pragma unroll
+      for (int i = 0; i < V; ++i) v.v[i] += acc[tk][i];
+      v.store(p);
+    }
+  }
+}
+
+// part[tile][m][e] = sum over the tile's tokens of x[t,m] * dl[t,e]; grid (tile, m block, expert chunk)
+template <typename T>
+__global__ __launch_bounds__(kDwThreads) void gate_dw_partial_kernel(const T* __restrict__ x,
+                                                                     const float* __restrict__ dl,
+                                                                     float* __restrict__ part, int n_tokens,
+                                                                     int d_model, int n_experts) {
+  constexpr int V = Elem<T>::kVec;
+  constexpr int kSub = 64;
+  __shared__ float dls[kSub][kEc];
+  const int t0 = blockIdx.x * kDwTokens;
+  const int m = (blockIdx.y * kDwThreads + threadIdx.x) * V;
+  const int ec = blockIdx.z * kEc;
+  float acc[V][kEc];
+#pragma unroll
+  for (int i = 0; i < V; ++i)
+#pragma unroll
+    for (int e = 0; e < kEc; ++e) acc[i][e] = 0.0f;
+  for (int ts = 0; ts < kDwTokens; ts += kSub) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < kSub * kEc; i += kDwThreads) {
+      int tk = i / kEc, e = i % kEc;
+      int t = t0 + ts + tk;
+      dls[tk][e] = (t < n_tokens && ec + e < n_experts) ? dl[(size_t)t * n_experts + ec + e] : 0.0f;
+    }
+    __syncthreads();
+    if (m < d_model) {
+      for (int tk = 0; tk < kSub; ++tk) {
+        int t = t0 + ts + tk;
+        if (t >= n_tokens) break;
+        Vec16<T> xv;
+        xv.load(x + (size_t)t * d_model + m);
+#pragma unroll
+        for (int e = 0; e < kEc; ++e) {
+          const float d = dls[tk][e];
+#pragma unroll
+          for (int i = 0; i < V; ++i) acc[i][e] = fmaf(xv.v[i], d, acc[i][e]);
+        }
+      }
+    }
+  }
+  if (m < d_model) {
+    float* p = part + ((size_t)blockIdx.x * d_model + m) * n_experts;
+#pragma unroll
+    for (int i = 0; i < V; ++i)
+#pragma unroll
+      for (int e = 0; e < kEc; ++e)
+        if (ec + e < n_experts) p[(size_t)i * n_experts + ec + e] = acc[i][e];
+  }
+}
+
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __restrict__ dl, float* __restrict__ bpart,
+                                                             int n_tokens, int n_experts) {
+  // block = one token tile; thread e sums its column over the tile in token order
+  const int t0 = blockIdx.x * kDwTokens;
+  for (int e = threadIdx.x; e < n_experts; e += 256) {
+    float s = 0.0f;
+    for (int tk = 0; tk < kDwTokens && t0 + tk < n_tokens; ++tk) s += dl[(size_t)(t0 + tk) * n_experts + e];
+    bpart[(size_t)blockIdx.x * n_experts + e] = s;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __restrict__ part,
+                                                             const float* __restrict__ bpart, T* __restrict__ dw_gate,
+                                                             float* __restrict__ db_gate, int ntile, int d_model,
+                                                             int n_experts) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int n = d_model * n_experts;
+  if (i < n) {
+    float s = 0.0f;
+    for (int tl = 0; tl < ntile; ++tl) s += part[(size_t)tl * n + i];
+    Elem<T>::st(dw_gate + i, s);
+  }
+  if (db_gate != nullptr && i < n_experts) {
+    float s = 0.0f;
+    for (int tl = 0; tl < ntile; ++tl) s += bpart[(size_t)tl * n_experts + i];
+    db_gate[i] = s;
+  }
+}
+
+template <typename T>
+moe_status_t route_bwd_t(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
+                         const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                         float* db_gate, void* dx, void* ws, hipStream_t s) {
+  constexpr int V = Elem<T>::kVec;
+  RouteBwdPlan p = route_bwd_plan(c);
+  unsigned char* w = static_cast<unsigned char*>(ws);
+  float* dl = reinterpret_cast<float*>(w + p.off_dl);
+  float* part = reinterpret_cast<float*>(w + p.off_part);
+  float* bpart = reinterpret_cast<float*>(w + p.off_bpart);
+  const size_t ne = (size_t)c.n_tokens * c.n_experts;
+  hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
+                     dl, c.n_tokens, c.n_experts, c.top_k);
+  MOE_CHECK_LAUNCH();
+  hipLaunchKernelGGL(gate_dx_kernel<T>, dim3(ceil_div(c.n_tokens, kDxTokens), ceil_div(c.d_model, 256 * V)), dim3(256),
+                     (size_t)kDxTokens * c.n_experts * sizeof(float), s, dl, (const T*)w_gate, (T*)dx, c.n_tokens,
+                     c.d_model, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  hipLaunchKernelGGL(gate_dw_partial_kernel<T>,
+                     dim3(p.ntile, ceil_div(c.d_model, kDwThreads * V), ceil_div(c.n_experts, kEc)), dim3(kDwThreads), 0,
+                     s, (const T*)x, dl, part, c.n_tokens, c.d_model, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  if (db_gate != nullptr) {
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3(p.ntile), dim3(256), 0, s, dl, bpart, c.n_tokens, c.n_experts);
+    MOE_CHECK_LAUNCH();
+  }
+  hipLaunchKernelGGL(gate_dw_reduce_kernel<T>, dim3(ceil_div(c.d_model * c.n_experts, 256)), dim3(256), 0, s, part, bpart,
+                     (T*)dw_gate, db_gate, p.ntile, c.d_model, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
+}
+
+}  // namespace
+
+size_t route_workspace_bytes(const moe_config_t& c) { return route_plan(c).bytes; }
+size_t route_bwd_workspace_bytes(const moe_config_t& c) { return route_bwd_plan(c).bytes; }
+
+moe_status_t launch_route(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
+                          float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
+                          int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
+  return c.dtype == MOE_BF16 ? route_t<bf16_t>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
+                                               offsets, src_of_row, ws, s)
+                             : route_t<float>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
+                                              offsets, src_of_row, ws, s);
+}
+
+moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
+                              const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                              float* db_gate, void* dx, void* ws, hipStream_t s) {
+  return c.dtype == MOE_BF16
+             ? route_bwd_t<bf16_t>(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s)
+             : route_bwd_t<float>(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s);
+}
+
+}  // namespace moe

@@ -1,0 +1,83 @@
+"""Host-side checks of the C-ABI boundary that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments with status codes before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2501_10714_amd as moe
+from paper_2501_10714_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(moe.lib_path()):
+        from paper_2501_10714_amd import build
+        build.build()
+    return moe.load()
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "moe_mi355x.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = header_functions()
+    assert set(names) == set(binding.ENTRY_POINTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_capacity_matches_formula(lib):
+    assert moe.moe_capacity(256, 4, 1, 1.25) == 80
+    assert moe.moe_capacity(8192, 16, 2, 1.2) == 1229
+    assert moe.moe_capacity(32768, 64, 6, 1.5) == 4608
+    assert moe.moe_capacity(65536, 32, 1, 1.0) == 2048
+    assert moe.moe_capacity(0, 4, 1, 1.0) == -1 and moe.moe_capacity(8, 4, 1, -1.0) == -1
+
+
+def test_config_validation(lib):
+    ok = moe.MoeConfig.make(64, 64, 4, 128, 2, 0, moe.DT_F32, moe.ACT_RELU)
+    ws, sv = moe.moe_workspace_bytes(ok)
+    assert ws > 0 and sv > 0
+    bad = [dict(N=0), dict(k=5), dict(dtype=7), dict(act=9), dict(M=66), dict(E=300, k=2), dict(k=9, E=16)]
+    for kw in bad:
+        a = dict(N=64, M=64, E=4, H=128, k=2, capacity=0, dtype=moe.DT_F32, act=moe.ACT_RELU)
+        a.update(kw)
+        with pytest.raises(moe.MoeError):
+            moe.moe_workspace_bytes(moe.MoeConfig.make(**a))
+        assert moe.moe_last_error() != ""
+
+
+def test_null_pointers_are_rejected_before_any_launch(lib):
+    cfg = moe.MoeConfig.make(64, 64, 4, 128, 2, 0, moe.DT_F32, moe.ACT_RELU)
+    null = C.c_void_p(0)
+    st = lib.moe_dispatch(C.byref(cfg), null, null, null, null)
+    assert st == 1 and "NULL" in moe.moe_last_error()
+    st = lib.moe_route(C.byref(cfg), *([null] * 13), C.c_size_t(0), null)
+    assert st == 1
+    st = lib.moe_layer_fwd(None, *([null] * 8), C.c_size_t(0), null, C.c_size_t(0), null)
+    assert st == 1 and "cfg" in moe.moe_last_error()
+    # workspace too small: status 3 (fake non-NULL pointers are never dereferenced on the host)
+    fake = C.c_void_p(4096)
+    st = lib.moe_route(C.byref(cfg), *([fake] * 13), C.c_size_t(16), null)
+    assert st == 3 and "workspace" in moe.moe_last_error()
+    glu = moe.MoeConfig.make(64, 64, 4, 128, 2, 0, moe.DT_F32, moe.ACT_SWIGLU)
+    st = lib.moe_expert_ffn_fwd(C.byref(glu), fake, fake, fake, null, fake, fake, fake, fake, fake, null, C.c_size_t(0), null)
+    assert st == 1 and "w3" in moe.moe_last_error()
+
+
+def test_saved_layout_is_disjoint_and_ordered(lib):
+    cfg = moe.MoeConfig.make(100, 64, 4, 128, 2, 0, moe.DT_BF16, moe.ACT_SWIGLU)
+    _, total = moe.moe_workspace_bytes(cfg)
+    end = 0
+    for name in moe.SAVED:
+        off, n = moe.moe_saved_offset(cfg, name)
+        assert off >= end and off % 256 == 0
+        end = off + n
+    assert end <= total

@@ -1,0 +1,263 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle, element by element, on seeded inputs
+whose sizes span several tiles and ragged tails.  Inputs of each call come from the input generator
+or from the oracle (rounded to the storage format), never from another HIP call.
+
+Bars: routing integers bit exact; fp32 tensors 1e-5, bf16 tensors 2e-2 (max |gpu-oracle| / max |oracle|
+per tensor).  Gate logits must equal the oracle's fp32 values bit for bit (both sides round one
+fp64-accumulated sum)."""
+import numpy as np
+import pytest
+import torch
+
+import moe_synth as S
+import paper_2501_10714_amd as moe
+from oracle import moe_oracle as O
+from moe_harness import (TOL, Buffers, assert_routing_equal, cap_of, dev_inputs, f64_inputs, make_cfg, oracle_layer,
+                         rel_err, run_layer, saved_np, store, to_dev, to_np)
+
+pytestmark = pytest.mark.gpu
+
+W = S.WORKLOADS
+CASES = {
+    # name: workload scaled to a size the oracle finishes in seconds; tiles: MFMA 256x256x64, route 64 tokens
+    "tiny_full": W["tiny"],
+    "f32_ragged": S.scaled(W["tiny"], N=333, M=72, H=100, E=5, k=2, f=1.1, seed=11),
+    "f32_gelu_resid": S.scaled(W["switch"], N=500, M=64, H=96, E=8, dtype=S.DT_F32, seed=12),
+    "f32_glu_renorm": S.scaled(W["mixtral"], N=300, M=48, H=80, E=4, dtype=S.DT_F32, seed=13),
+    "gpt2_small": S.scaled(W["gpt2"], N=1500, M=256, H=320, E=4, seed=21),       # 750 rows/expert: 3 row tiles, ragged
+    "mixtral_small": S.scaled(W["mixtral"], N=1100, M=192, H=448, E=4, seed=22),  # no drop, renormalised, SwiGLU
+    "fine_small": S.scaled(W["finegrained"], N=700, M=128, H=136, E=16, k=6, seed=23),  # H%64 != 0: plain GEMM for K=H
+    "switch_small": S.scaled(W["switch"], N=2000, M=128, H=256, E=8, seed=24),    # top-1, f=1, residual, Zipf bias
+    "erf_odd": S.scaled(W["gpt2"], N=130, M=72, H=88, E=3, k=3, act=S.ACT_GELU_ERF, seed=25),  # nothing tile aligned
+}
+
+
+def routing_dict(b):
+    return {n: to_np(getattr(b, n)) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}
+
+
+@pytest.fixture(scope="module")
+def solved():
+    cache = {}
+
+    def get(name):
+        if name not in cache:
+            w = CASES[name]
+            d = S.draw_all(w)
+            cache[name] = (w, d) + oracle_layer(w, d)
+        return cache[name]
+    return get
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_route(name, solved):
+    w, d, f, fwd, bwd = solved(name)
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    dd = dev_inputs(d)
+    moe.moe_route(cfg, dd["x"], dd["w_gate"], dd["b_gate"], b.logits, b.probs, b.topk_idx, b.topk_w, b.pos, b.row_of,
+                  b.count, b.offsets, b.src_of_row, b.ws)
+    torch.cuda.synchronize()
+    logits = b.logits.cpu().numpy()
+    assert np.array_equal(logits, fwd["logits"]), f"{np.count_nonzero(logits != fwd['logits'])} logits differ in bits"
+    assert_routing_equal(routing_dict(b), fwd)
+    assert rel_err(to_np(b.probs), fwd["probs"]) <= 1e-5
+    assert rel_err(to_np(b.topk_w), fwd["topk_w"]) <= 1e-5
+    if w.f is not None:
+        assert int(b.count.max()) <= cap_of(w)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_dispatch_and_combine(name, solved):
+    w, d, f, fwd, bwd = solved(name)
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    dd = dev_inputs(d)
+    A = int(fwd["offsets"][-1])
+    row_of = to_dev(fwd["row_of"])
+    moe.moe_dispatch(cfg, dd["x"], row_of, b.xe)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(b.xe[:A]), fwd["xe"]), "dispatch is a pure copy"
+    # combine on the oracle's expert outputs (rounded to storage)
+    q_st = store(fwd["q"], w)
+    q_dev = torch.zeros_like(b.q); q_dev[:A] = to_dev(q_st)
+    topk_w = to_dev(fwd["topk_w"].astype(np.float32))
+    moe.moe_combine(cfg, q_dev, topk_w, row_of, dd["x"], b.y)
+    want = O.inverse_order(S.to_f64(q_st), fwd["topk_w"].astype(np.float32).astype(np.float64), fwd["row_of"],
+                           f["x"] if w.add_residual else None)
+    assert rel_err(to_np(b.y), want) <= TOL[w.dtype] * (0.25 if w.dtype == S.DT_BF16 else 1)
+    dropped_all = np.all(fwd["pos"] < 0, axis=1)
+    if dropped_all.any() and not w.add_residual:
+        assert np.all(to_np(b.y)[dropped_all] == 0)
+    # combine backward
+    moe.moe_combine_bwd(cfg, dd["dy"], q_dev, topk_w, row_of, b.dq, b.dtopk_w)
+    dq, dtw = O.inverse_order_bwd(f["dy"], S.to_f64(q_st), fwd["topk_w"].astype(np.float32).astype(np.float64), fwd["row_of"])
+    assert rel_err(to_np(b.dq[:A]), dq) <= TOL[w.dtype] * (0.25 if w.dtype == S.DT_BF16 else 1)
+    assert rel_err(to_np(b.dtopk_w), dtw) <= 1e-5
+    assert np.all(to_np(b.dtopk_w)[fwd["pos"] < 0] == 0)
+    # dispatch backward on the oracle's dxe
+    dxe_st = store(bwd["dxe"], w)
+    dxe_dev = torch.zeros_like(b.dxe); dxe_dev[:A] = to_dev(dxe_st)
+    moe.moe_dispatch_bwd(cfg, dxe_dev, row_of, dd["dy"] if w.add_residual else None, b.dx)
+    want = O.order_bwd(S.to_f64(dxe_st), fwd["row_of"], f["dy"] if w.add_residual else None)
+    assert rel_err(to_np(b.dx), want) <= TOL[w.dtype] * (0.25 if w.dtype == S.DT_BF16 else 1)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_expert_ffn(name, solved):
+    w, d, f, fwd, bwd = solved(name)
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    dd = dev_inputs(d)
+    A = int(fwd["offsets"][-1])
+    tol = TOL[w.dtype]
+    offsets = to_dev(fwd["offsets"])
+    xe_dev = torch.zeros_like(b.xe); xe_dev[:A] = to_dev(store(fwd["xe"], w))
+    moe.moe_expert_ffn_fwd(cfg, xe_dev, offsets, dd["w1"], dd["w3"], dd["w2"], b.q, b.a1, b.a3, b.hh, b.ws)
+    torch.cuda.synchronize()
+    a1, a3, hh = fwd["saved"]
+    assert rel_err(to_np(b.a1[:A]), a1) <= tol
+    assert rel_err(to_np(b.hh[:A]), hh) <= tol
+    if w.gated:
+        assert rel_err(to_np(b.a3[:A]), a3) <= tol
+    assert rel_err(to_np(b.q[:A]), fwd["q"]) <= tol
+    # backward from the oracle's stored activations and dq (rounded to storage)
+    st = {n: store(v, w) for n, v in (("dq", bwd["dq"]), ("a1", a1), ("hh", hh))}
+    if w.gated:
+        st["a3"] = store(a3, w)
+    devs = {}
+    for n, v in st.items():
+        t = torch.zeros(w.N * w.k, v.shape[1], dtype=b.q.dtype, device="cuda"); t[:A] = to_dev(v); devs[n] = t
+    moe.moe_expert_ffn_bwd(cfg, devs["dq"], xe_dev, offsets, dd["w1"], dd["w3"], dd["w2"], devs["a1"], devs.get("a3"),
+                           devs["hh"], b.dxe, b.dw1, b.dw3, b.dw2, b.ws)
+    torch.cuda.synchronize()
+    s64 = {n: S.to_f64(v) for n, v in st.items()}
+    dxe, dw1, dw3, dw2 = O.expert_ffn_bwd(s64["dq"], fwd["xe"], fwd["offsets"], f["w1"], f["w3"], f["w2"],
+                                          (s64["a1"], s64.get("a3"), s64["hh"]), w.act)
+    assert rel_err(to_np(b.dxe[:A]), dxe) <= tol
+    assert rel_err(to_np(b.dw1), dw1) <= tol
+    assert rel_err(to_np(b.dw2), dw2) <= tol
+    if w.gated:
+        assert rel_err(to_np(b.dw3), dw3) <= tol
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_route_bwd(name, solved):
+    w, d, f, fwd, bwd = solved(name)
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    dd = dev_inputs(d)
+    probs32 = fwd["probs"].astype(np.float32)
+    dtw32 = bwd["dtopk_w"].astype(np.float32)
+    base = store(np.zeros((w.N, w.M)) + 0.5 * f["dy"], w)       # something already in dx: the call accumulates
+    b.dx.copy_(to_dev(base))
+    moe.moe_route_bwd(cfg, dd["x"], dd["w_gate"], to_dev(probs32), to_dev(fwd["topk_idx"]), to_dev(fwd["pos"]),
+                      to_dev(dtw32), b.dw_gate, b.db_gate if d["b_gate"] is not None else None, b.dx, b.ws)
+    torch.cuda.synchronize()
+    n, e = probs32.shape
+    g = np.zeros((n, e))
+    for t in range(n):
+        for j in range(w.k):
+            if fwd["pos"][t, j] >= 0:
+                g[t, fwd["topk_idx"][t, j]] = dtw32[t, j]
+    p = probs32.astype(np.float64)
+    dl = p * (g - (g * p).sum(1, keepdims=True))
+    tol = TOL[w.dtype]
+    assert rel_err(to_np(b.dw_gate), f["x"].T @ dl) <= tol
+    assert rel_err(to_np(b.dx), S.to_f64(base) + dl @ f["w_gate"].T) <= tol
+    if d["b_gate"] is not None:
+        assert rel_err(to_np(b.db_gate), dl.sum(0)) <= 1e-5 * 10
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_layer_fwd_bwd(name, solved):
+    w, d, f, fwd, bwd = solved(name)
+    cfg, b = run_layer(w, d)
+    tol = TOL[w.dtype]
+    got = {n: saved_np(cfg, b, n, torch.int32) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}
+    got = {n: v.reshape(np.asarray(fwd[n]).shape) for n, v in got.items()}
+    assert_routing_equal(got, fwd)
+    assert np.array_equal(saved_np(cfg, b, "logits", torch.float32).reshape(w.N, w.E), fwd["logits"].astype(np.float64))
+    assert rel_err(to_np(b.y), fwd["y"]) <= tol
+    assert rel_err(to_np(b.dx), bwd["dx"]) <= tol
+    assert rel_err(to_np(b.dw_gate), bwd["dw_gate"]) <= tol
+    assert rel_err(to_np(b.dw1), bwd["dw1"]) <= tol
+    assert rel_err(to_np(b.dw2), bwd["dw2"]) <= tol
+    if w.gated:
+        assert rel_err(to_np(b.dw3), bwd["dw3"]) <= tol
+    if d["b_gate"] is not None:
+        assert rel_err(to_np(b.db_gate), bwd["db_gate"]) <= tol
+    # run to run: bit identical
+    y1, dx1, dw1 = b.y.clone(), b.dx.clone(), b.dw1.clone()
+    cfg, b = run_layer(w, d, bufs=b)
+    assert torch.equal(y1, b.y) and torch.equal(dx1, b.dx) and torch.equal(dw1, b.dw1)
+
+
+def test_plain_and_mfma_gemm_agree_with_oracle(solved, monkeypatch):
+    """The bf16 MFMA path and the plain FMA path are both held to the oracle on the same case."""
+    w, d, f, fwd, bwd = solved("mixtral_small")
+    monkeypatch.setenv("MOE_FORCE_PLAIN_GEMM", "1")
+    cfg, b = run_layer(w, d)
+    for name, want in (("y", fwd["y"]), ("dx", bwd["dx"]), ("dw1", bwd["dw1"]), ("dw2", bwd["dw2"]), ("dw3", bwd["dw3"])):
+        assert rel_err(to_np(getattr(b, name)), want) <= TOL[w.dtype], name
+
+
+# ----------------------------------------------------------------------------- edge cases
+
+def test_expert_without_tokens_and_accumulate():
+    # 9 tokens, 16 experts, top-1: most experts stay empty; their weight gradients must be zero
+    w = S.scaled(W["gpt2"], N=9, M=64, H=64, E=16, k=1, f=None, seed=31)
+    d = S.draw_all(w)
+    f, fwd, bwd = oracle_layer(w, d)
+    assert (fwd["count"] == 0).any()
+    cfg, b = run_layer(w, d)
+    got = {n: saved_np(cfg, b, n, torch.int32).reshape(np.asarray(fwd[n]).shape) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}
+    assert_routing_equal(got, fwd)
+    dw1 = to_np(b.dw1)
+    assert np.all(dw1[fwd["count"] == 0] == 0)
+    assert rel_err(dw1, bwd["dw1"]) <= TOL[w.dtype]
+    # accumulate_wgrad: a second backward adds the same gradient again
+    first = {n: getattr(b, n).float().clone() for n in ("dw1", "dw2")}
+    cfg2, b = run_layer(w, d, accumulate=1, bufs=b)
+    for n in ("dw1", "dw2"):
+        assert rel_err(to_np(getattr(b, n)), 2 * first[n].cpu().numpy().astype(np.float64)) <= TOL[w.dtype]
+
+
+def test_capacity_one_drops_almost_everything():
+    w = S.scaled(W["switch"], N=200, M=64, H=64, E=4, seed=32)
+    d = S.draw_all(w)
+    f, fwd, bwd = oracle_layer(w, d, capacity=1)
+    assert int(fwd["offsets"][-1]) <= 4
+    cfg, b = run_layer(w, d, capacity=1)
+    got = {n: saved_np(cfg, b, n, torch.int32).reshape(np.asarray(fwd[n]).shape) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}
+    assert_routing_equal(got, fwd)
+    assert rel_err(to_np(b.y), fwd["y"]) <= TOL[w.dtype]
+    assert rel_err(to_np(b.dx), bwd["dx"]) <= TOL[w.dtype]
+    dropped = np.all(fwd["pos"] < 0, axis=1)
+    assert np.array_equal(to_np(b.y)[dropped], f["x"][dropped])      # residual passthrough, exact
+
+
+def test_all_experts_selected_identical_experts_is_dense_ffn():
+    # k = E, identical experts, renormalised gate: the layer is the dense FFN (weights sum to 1)
+    w = S.scaled(W["mixtral"], N=96, M=64, H=128, E=4, k=4, dtype=S.DT_F32, seed=33)
+    d = S.draw_all(w)
+    for n in ("w1", "w2", "w3"):
+        d[n] = np.ascontiguousarray(np.broadcast_to(d[n][:1], d[n].shape))
+    cfg, b = run_layer(w, d)
+    x = d["x"].astype(np.float64)
+    a1, a3 = x @ d["w1"][0].astype(np.float64), x @ d["w3"][0].astype(np.float64)
+    dense = (a1 / (1 + np.exp(-a1)) * a3) @ d["w2"][0].astype(np.float64)
+    assert rel_err(to_np(b.y), dense) <= 1e-5
+
+
+def test_exact_ties_go_to_the_lower_expert():
+    w = S.scaled(W["gpt2"], N=70, M=64, H=64, E=6, k=2, f=None, seed=34)
+    d = S.draw_all(w)
+    d["w_gate"][:, 3] = d["w_gate"][:, 1]          # experts 1 and 3 always tie
+    d["w_gate"][:, 5] = d["w_gate"][:, 1]
+    f, fwd, bwd = oracle_layer(w, d)
+    cfg, b = run_layer(w, d)
+    got = {n: saved_np(cfg, b, n, torch.int32).reshape(np.asarray(fwd[n]).shape) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}
+    assert_routing_equal(got, fwd)
+    idx = fwd["topk_idx"]
+    assert not np.any((idx[:, 0] == 3) | (idx[:, 0] == 5))
