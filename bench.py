@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the single-GPU MoE layer hot path (forward + backward) on one MI355X.
+
+A step is one pass of the whole path -- gate/top-k/capacity, dispatch, expert FFNs (grouped GEMM),
+combine, and the full backward -- over one batch of synthetic tokens already resident in HBM.
+Prints ONE JSON line: whole-job tokens/s, the roofline of the dominant kernel family (the bf16 MFMA
+grouped GEMM of the experts, timed live with HIP events) and the CPU oracle timed on a bounded
+sample of the same workload on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="mixtral", choices=["tiny", "gpt2", "mixtral", "finegrained", "switch"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-breakdown", action="store_true")
+    return ap.parse_args()
+
+
+def device_inputs(w, torch):
+    """Synthetic inputs drawn on the device (same shapes and distributions as the parity inputs)."""
+    import moe_synth as S
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1000 + w.seed)
+    dt = torch.bfloat16 if w.dtype == S.DT_BF16 else torch.float32
+
+    def normal(shape, std):
+        out = torch.empty(shape, dtype=dt, device="cuda")
+        flat = out.view(-1)
+        step = 1 << 26
+        for i in range(0, flat.numel(), step):          # chunked: no fp32 temporary of the whole tensor
+            n = min(step, flat.numel() - i)
+            flat[i:i + n] = (torch.randn(n, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
+        return out
+
+    d = {"x": normal((w.N, w.M), w.x_std), "dy": normal((w.N, w.M), w.x_std), "w_gate": normal((w.M, w.E), 0.02),
+         "w1": normal((w.E, w.M, w.H), 0.02), "w2": normal((w.E, w.H, w.M), 0.02),
+         "w3": normal((w.E, w.M, w.H), 0.02) if w.gated else None}
+    bg = S.draw_b_gate(w)
+    d["b_gate"] = None if bg is None else torch.from_numpy(bg).cuda()
+    return d
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is the one-GPU hot path; it has no multi-GPU mode (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import moe_synth as S
+    import paper_2501_10714_amd as moe
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from moe_harness import Buffers, cap_of, make_cfg
+
+    moe.load()                                           # fails loudly when the HIP library is missing
+    torch.cuda.set_device(0)
+    w = S.WORKLOADS[args.workload]
+    cfg = make_cfg(w)
+    d = device_inputs(w, torch)
+    b = Buffers(w, cfg)
+    has_bias = d["b_gate"] is not None
+
+    def fwd():
+        moe.moe_layer_fwd(cfg, d["x"], d["w_gate"], d["b_gate"], d["w1"], d["w3"], d["w2"], b.y, b.saved, b.ws)
+
+    def bwd():
+        moe.moe_layer_bwd(cfg, d["dy"], d["x"], d["w_gate"], d["w1"], d["w3"], d["w2"], b.saved, b.dx, b.dw_gate,
+                          b.db_gate if has_bias else None, b.dw1, b.dw3, b.dw2, b.ws)
+
+    for _ in range(args.warmup):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- kept rows (A) and algorithmic work of the expert GEMMs
+    offs = moe.saved_view(cfg, b.saved, "offsets", torch.int32).cpu().numpy()
+    count = np.diff(offs)
+    A = int(offs[-1])
+    per_row = (6 if w.gated else 4) * w.M * w.H           # forward FLOP per kept row
+    flop_fwd, flop_bwd = A * per_row, 2 * A * per_row
+
+    # ---- per-call timing with HIP events on the launch stream (torch's current stream)
+    def timed(fn, reps):
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn(); torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(reps):
+            fn()
+        ev1.record(); torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / reps
+
+    sv = lambda name, dt: moe.saved_view(cfg, b.saved, name, dt)
+    tdt = b.y.dtype
+    i32, f32 = torch.int32, torch.float32
+    xe = sv("xe", tdt).view(w.N * w.k, w.M); q = sv("q", tdt).view(w.N * w.k, w.M)
+    a1 = sv("a1", tdt).view(w.N * w.k, w.H); hh = sv("hh", tdt).view(w.N * w.k, w.H)
+    a3 = sv("a3", tdt).view(w.N * w.k, w.H) if w.gated else None
+    row_of = sv("row_of", i32); offsets = sv("offsets", i32); topk_w = sv("topk_w", f32)
+    reps = max(3, args.steps // 2)
+    t_ffn_fwd = timed(lambda: moe.moe_expert_ffn_fwd(cfg, xe, offsets, d["w1"], d["w3"], d["w2"], b.q, b.a1, b.a3, b.hh, b.ws), reps)
+    moe.moe_combine_bwd(cfg, d["dy"], q, topk_w, row_of, b.dq, b.dtopk_w)
+    t_ffn_bwd = timed(lambda: moe.moe_expert_ffn_bwd(cfg, b.dq, xe, offsets, d["w1"], d["w3"], d["w2"], a1, a3, hh,
+                                                     b.dxe, b.dw1, b.dw3, b.dw2, b.ws), reps)
+    gemm_ms = t_ffn_fwd + t_ffn_bwd
+    achieved = (flop_fwd + flop_bwd) / (gemm_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gg_mfma_kernel (bf16 grouped GEMM, 2 forward + 4 backward launches per step)",
+                "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "flop_per_step": flop_fwd + flop_bwd, "ms_per_step": round(gemm_ms, 3),
+                "fwd": {"ms": round(t_ffn_fwd, 3), "tflops": round(flop_fwd / t_ffn_fwd / 1e9, 1)},
+                "bwd": {"ms": round(t_ffn_bwd, 3), "tflops": round(flop_bwd / t_ffn_bwd / 1e9, 1)}}
+
+    out = {"metric": "MoE layer fwd+bwd tokens/s (%s-shape, 1 GPU)" % w.name, "value": round(w.N / (ms_per_step * 1e-3), 1),
+           "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if w.dtype == S.DT_BF16 else "f32", "data": "synthetic",
+           "config": {"workload": "%s: N=%d M=%d E=%d H=%d k=%d f=%s act=%d renormalize=%d residual=%d" % (
+               w.name, w.N, w.M, w.E, w.H, w.k, S.capacity_factor_text(w), w.act, w.renormalize, w.add_residual),
+               "kept_rows": A, "rows_per_expert_min_max": [int(count.min()), int(count.max())]},
+           "expert_gemm_tflops": round(achieved, 1), "roofline": roofline}
+
+    if not args.no_breakdown:
+        bpe = 2 if w.dtype == S.DT_BF16 else 4
+        N, M, E, k = w.N, w.M, w.E, w.k
+        calls = {
+            "route": (lambda: moe.moe_route(cfg, d["x"], d["w_gate"], d["b_gate"], b.logits, b.probs, b.topk_idx, b.topk_w,
+                                            b.pos, b.row_of, b.count, b.offsets, b.src_of_row, b.ws),
+                      N * M * bpe + M * E * bpe + N * (8 * E + 16 * k) + 4 * (2 * E + 1)),
+            "dispatch": (lambda: moe.moe_dispatch(cfg, d["x"], row_of, b.xe), N * M * bpe + 4 * N * k + A * M * bpe),
+            "combine": (lambda: moe.moe_combine(cfg, q, topk_w, row_of, d["x"], b.y), A * M * bpe + 8 * N * k + N * M * bpe),
+            "combine_bwd": (lambda: moe.moe_combine_bwd(cfg, d["dy"], q, topk_w, row_of, b.dq, b.dtopk_w),
+                            N * M * bpe + 2 * A * M * bpe + 4 * N * k),
+            "dispatch_bwd": (lambda: moe.moe_dispatch_bwd(cfg, b.dxe, row_of, d["dy"], b.dx), A * M * bpe + N * M * bpe),
+            "route_bwd": (lambda: moe.moe_route_bwd(cfg, d["x"], d["w_gate"], sv("probs", f32), sv("topk_idx", i32),
+                                                    sv("pos", i32), b.dtopk_w, b.dw_gate,
+                                                    b.db_gate if has_bias else None, b.dx, b.ws),
+                          3 * N * M * bpe + 8 * N * E + M * E * bpe),
+        }
+        br = {}
+        for name, (fn, nbytes) in calls.items():
+            ms = timed(fn, reps)
+            br[name] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1), "hbm_frac": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 3)}
+        br["expert_ffn_fwd"] = {"ms": round(t_ffn_fwd, 3)}
+        br["expert_ffn_bwd"] = {"ms": round(t_ffn_bwd, 3)}
+        out["breakdown"] = br
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(w):
+    """The oracle, as it stands, timed on the host cores on a bounded sample of the workload: the same
+    layer (full d_model, d_hidden, k, activation, gate) on fewer tokens and, to bound the weight
+    memory, on min(E, max(k, 2)) experts.  Per-token arithmetic is that of the full workload."""
+    import numpy as np
+    import moe_synth as S
+    from oracle import moe_oracle as O
+    try:
+        import threadpoolctl
+        cores = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+    except Exception:
+        cores = os.cpu_count() or 1
+    e_s = min(w.E, max(w.k, 2))
+    per_token = 3 * (6 if w.gated else 4) * w.M * w.H * w.k      # fwd+bwd FLOP per token
+    n_s = int(max(64, min(w.N, 1.5e13 / per_token)))             # about 15 TFLOP of fp64 work
+    ws = S.scaled(w, N=n_s, E=e_s, f=None, bias="none")
+    d = S.draw_all(ws)
+    f = {k: (None if v is None else S.to_f64(v)) for k, v in d.items()}
+    t0 = time.perf_counter()
+    fwd = O.layer_fwd(f["x"], f["w_gate"], None, f["w1"], f["w3"], f["w2"], ws.k, 0, ws.act, ws.renormalize, ws.add_residual)
+    O.layer_bwd(f["dy"], f["x"], f["w_gate"], None, f["w1"], f["w3"], f["w2"], fwd, ws.act, ws.renormalize, ws.add_residual)
+    dt = time.perf_counter() - t0
+    return {"value": round(n_s / dt, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d tokens, %d of %d experts, full M=%d H=%d k=%d, fwd+bwd in fp64 numpy, %.1f s" % (
+                n_s, e_s, w.E, w.M, w.H, w.k, dt)}
+
+
+if __name__ == "__main__":
+    main()
