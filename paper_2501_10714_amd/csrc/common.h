@@ -66,11 +66,14 @@ __device__ __forceinline__ float silu_gradf_(float z) {
   float s = sigmoidf_(z);
   return s * (1.0f + z * (1.0f - s));
 }
+// tanh through one exponential: tanh(u) = 1 - 2 / (1 + e^{2u}); saturates cleanly for large |u|
+__device__ __forceinline__ float tanh_fast(float u) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * u)); }
+
 __device__ __forceinline__ float act_fwd(float z, int act) {
   if (act == MOE_ACT_RELU) return z > 0.0f ? z : 0.0f;
   if (act == MOE_ACT_GELU_TANH) {
     float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
-    return 0.5f * z * (1.0f + tanhf(u));
+    return 0.5f * z * (1.0f + tanh_fast(u));
   }
   return 0.5f * z * (1.0f + erff(z * 0.7071067811865476f));
 }
@@ -78,7 +81,7 @@ __device__ __forceinline__ float act_grad(float z, int act) {
   if (act == MOE_ACT_RELU) return z > 0.0f ? 1.0f : 0.0f;
   if (act == MOE_ACT_GELU_TANH) {
     float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
-    float th = tanhf(u);
+    float th = tanh_fast(u);
     return 0.5f * (1.0f + th) + 0.5f * z * (1.0f - th * th) * 0.7978845608028654f * (1.0f + 0.134145f * z * z);
   }
   return 0.5f * (1.0f + erff(z * 0.7071067811865476f)) + z * __expf(-0.5f * z * z) * 0.3989422804014327f;

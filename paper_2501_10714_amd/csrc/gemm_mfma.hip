@@ -34,6 +34,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // native vector: stays in registers (HIP's uint4 struct copies as memcpy)
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kThreads = 256;
@@ -83,10 +85,10 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
   return v.u;
 }
 __device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, float d) {
-  *reinterpret_cast<uint2*>(p) = make_uint2(pack2(a, b), pack2(c, d));
+  *reinterpret_cast<u32x2*>(p) = u32x2{pack2(a, b), pack2(c, d)};
 }
 __device__ __forceinline__ void load4(const bf16_t* p, float* v) {
-  uint2 r = *reinterpret_cast<const uint2*>(p);
+  u32x2 r = *reinterpret_cast<const u32x2*>(p);
   v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xFFFF0000u);
   v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xFFFF0000u);
 }
@@ -140,7 +142,7 @@ __device__ __forceinline__ TileId find_tile(const GemmP& p, int n_nt, int mt_fix
   return t;
 }
 
-template <int LA, int LB, int EPI, bool RAGGED_K>
+template <int LA, int LB, int EPI, bool RAGGED_K, int ACT>
 __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt, int mt_fix) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr bool kGluFwd = EPI == EPI_GLU_FWD;
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
     }
   }
 
-  uint4 areg[kSlots], breg[kSlots];
+  u32x4 areg[kSlots], breg[kSlots];
   auto fetch = [&](int it) {
     const int pr = it / nk1;
     const int k0 = (it - pr * nk1) * BK;
@@ -209,17 +211,17 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
 #pragma unroll
     for (int r = 0; r < kSlots; ++r) {
       if (LA == KC) {
-        areg[r] = *reinterpret_cast<const uint4*>(A + aoff[r] + k0);
+        areg[r] = *reinterpret_cast<const u32x4*>(A + aoff[r] + k0);
       } else {
         const int k = k0 + ((tid + kThreads * r) >> 5);
-        areg[r] = k < Kg ? *reinterpret_cast<const uint4*>(A + (long)(t.r0 + k) * lda + aoff[r]) : make_uint4(0, 0, 0, 0);
+        areg[r] = k < Kg ? *reinterpret_cast<const u32x4*>(A + (long)(t.r0 + k) * lda + aoff[r]) : u32x4{0u, 0u, 0u, 0u};
       }
       if (LB == KC) {
-        breg[r] = *reinterpret_cast<const uint4*>(B0 + boff[r] + k0);
+        breg[r] = *reinterpret_cast<const u32x4*>(B0 + boff[r] + k0);
       } else {
         int k = k0 + ((tid + kThreads * r) >> 5);
         if (RAGGED_K) k = t.r0 + min(k, Kg - 1);
-        breg[r] = *reinterpret_cast<const uint4*>((bsrc[r] ? B1 : B0) + (long)k * ldb + boff[r]);
+        breg[r] = *reinterpret_cast<const u32x4*>((bsrc[r] ? B1 : B0) + (long)k * ldb + boff[r]);
       }
     }
   };
@@ -228,8 +230,8 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
     unsigned char* b = a + kOperandBytes;
 #pragma unroll
     for (int r = 0; r < kSlots; ++r) {
-      *reinterpret_cast<uint4*>(a + alds[r]) = areg[r];
-      *reinterpret_cast<uint4*>(b + blds[r]) = breg[r];
+      *reinterpret_cast<u32x4*>(a + alds[r]) = areg[r];
+      *reinterpret_cast<u32x4*>(b + blds[r]) = breg[r];
     }
   };
 
@@ -301,8 +303,8 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
           store4(c, v[0], v[1], v[2], v[3]);
         } else if (EPI == EPI_ACT_FWD) {
           store4(static_cast<bf16_t*>(p.C[0]) + off, v[0], v[1], v[2], v[3]);
-          store4(static_cast<bf16_t*>(p.C[2]) + off, act_fwd(v[0], p.act), act_fwd(v[1], p.act), act_fwd(v[2], p.act),
-                 act_fwd(v[3], p.act));
+          store4(static_cast<bf16_t*>(p.C[2]) + off, act_fwd(v[0], ACT), act_fwd(v[1], ACT), act_fwd(v[2], ACT),
+                 act_fwd(v[3], ACT));
         } else if (EPI == EPI_GLU_FWD) {
           float g[4];
 #pragma unroll
@@ -314,8 +316,8 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         } else if (EPI == EPI_ACT_BWD) {
           float a1[4];
           load4(static_cast<const bf16_t*>(p.X[0]) + off, a1);
-          store4(static_cast<bf16_t*>(p.C[0]) + off, v[0] * act_grad(a1[0], p.act), v[1] * act_grad(a1[1], p.act),
-                 v[2] * act_grad(a1[2], p.act), v[3] * act_grad(a1[3], p.act));
+          store4(static_cast<bf16_t*>(p.C[0]) + off, v[0] * act_grad(a1[0], ACT), v[1] * act_grad(a1[1], ACT),
+                 v[2] * act_grad(a1[2], ACT), v[3] * act_grad(a1[3], ACT));
         } else {
           float a1[4], a3[4];
           load4(static_cast<const bf16_t*>(p.X[0]) + off, a1);
@@ -330,7 +332,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
   }
 }
 
-template <int LA, int LB, int EPI, bool RAGGED_K>
+template <int LA, int LB, int EPI, bool RAGGED_K, int ACT = 0>
 moe_status_t launch_cfg(const GemmP& p, hipStream_t s) {
   constexpr int out_cols = EPI == EPI_GLU_FWD ? BN / 2 : BN;
   const int n_nt = ceil_div(p.N, out_cols);
@@ -346,7 +348,7 @@ moe_status_t launch_cfg(const GemmP& p, hipStream_t s) {
   }
   if (max_tiles <= 0) return MOE_OK;
   static bool attr_set = false;
-  auto kern = gg_mfma_kernel<LA, LB, EPI, RAGGED_K>;
+  auto kern = gg_mfma_kernel<LA, LB, EPI, RAGGED_K, ACT>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        kLdsBytes);
@@ -378,9 +380,15 @@ moe_status_t launch_gemm_mfma(const GemmP& p, int epi, bool ragged_k, hipStream_
   switch (epi) {
     case EPI_PLAIN:
       return b_kc ? launch_cfg<KC, KC, EPI_PLAIN, false>(p, s) : launch_cfg<KC, TR, EPI_PLAIN, false>(p, s);
-    case EPI_ACT_FWD: return launch_cfg<KC, TR, EPI_ACT_FWD, false>(p, s);
+    case EPI_ACT_FWD:
+      if (p.act == MOE_ACT_RELU) return launch_cfg<KC, TR, EPI_ACT_FWD, false, MOE_ACT_RELU>(p, s);
+      if (p.act == MOE_ACT_GELU_TANH) return launch_cfg<KC, TR, EPI_ACT_FWD, false, MOE_ACT_GELU_TANH>(p, s);
+      return launch_cfg<KC, TR, EPI_ACT_FWD, false, MOE_ACT_GELU_ERF>(p, s);
     case EPI_GLU_FWD: return launch_cfg<KC, TR, EPI_GLU_FWD, false>(p, s);
-    case EPI_ACT_BWD: return launch_cfg<KC, KC, EPI_ACT_BWD, false>(p, s);
+    case EPI_ACT_BWD:
+      if (p.act == MOE_ACT_RELU) return launch_cfg<KC, KC, EPI_ACT_BWD, false, MOE_ACT_RELU>(p, s);
+      if (p.act == MOE_ACT_GELU_TANH) return launch_cfg<KC, KC, EPI_ACT_BWD, false, MOE_ACT_GELU_TANH>(p, s);
+      return launch_cfg<KC, KC, EPI_ACT_BWD, false, MOE_ACT_GELU_ERF>(p, s);
     default: return launch_cfg<KC, KC, EPI_GLU_BWD, false>(p, s);
   }
 }
