@@ -24,6 +24,8 @@
 // range tiles are ordered in bands of 8 row-tiles x all column-tiles so the 32 CUs of an XCD share
 // A and B panels in L2.  Rows are ragged per expert: the tile list is derived from offsets[] on
 // the device by every workgroup (E <= 256 scalar steps), no host synchronisation.
+#include <type_traits>
+
 #include "common.h"
 #include "gemm_params.h"
 
@@ -225,11 +227,12 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
       }
     }
   };
-  auto stash = [&](int stage) {
+  // half h of the prefetched tile -> LDS stage
+  auto stash_half = [&](int stage, int h) {
     unsigned char* a = lds + stage * kStageBytes;
     unsigned char* b = a + kOperandBytes;
 #pragma unroll
-    for (int r = 0; r < kSlots; ++r) {
+    for (int r = h * (kSlots / 2); r < (h + 1) * (kSlots / 2); ++r) {
       *reinterpret_cast<u32x4*>(a + alds[r]) = areg[r];
       *reinterpret_cast<u32x4*>(b + blds[r]) = breg[r];
     }
@@ -243,33 +246,65 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+  auto load_frags = [&](bf16x8(&af)[4], bf16x8(&bf)[4], const unsigned char* a, const unsigned char* b, int s) {
+#pragma unroll
+    for (int f = 0; f < 4; ++f) af[f] = read_frag<LA>(a, wm * 128 + f * 32, s, lane);
+#pragma unroll
+    for (int f = 0; f < 4; ++f) bf[f] = read_frag<LB>(b, wn * 128 + f * 32, s, lane);
+  };
+  auto mfma_step = [&](const bf16x8(&af)[4], const bf16x8(&bf)[4]) {
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < 4; ++fn)
+        acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[fn], af[fm], acc[fm][fn], 0, 0, 0);
+  };
+  // LDS reads of one k-step spread over the 16 MFMAs of the previous one
+  constexpr int kReads = (LA == KC ? 4 : 8) + (LB == KC ? 4 : 8);
+  auto interleave = [&](int ds_writes, int vmem) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, (kReads + 7) / 8, 0);  // DS reads
+      if (ds_writes) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // 1 DS write
+      if (vmem) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);       // 2 VMEM reads
+    }
+  };
+
+  // One K iteration on LDS stage `it & 1`.  While its 64 MFMAs run, the tile for iteration it+1
+  // (already in registers) goes to the other stage and the loads for iteration it+2 are issued.
+  // Straight-line code (no branches) so that the scheduler can interleave the four instruction kinds.
+  auto iteration = [&](int it, auto more_tag) {
+    constexpr bool kMore = decltype(more_tag)::value;
+    const unsigned char* a = lds + (it & 1) * kStageBytes;
+    const unsigned char* b = a + kOperandBytes;
+    bf16x8 af0[4], bf0[4], af1[4], bf1[4];
+    load_frags(af0, bf0, a, b, 0);
+    load_frags(af1, bf1, a, b, 1);
+    mfma_step(af0, bf0);  // k-step 0
+    interleave(0, 0);
+    load_frags(af0, bf0, a, b, 2);
+    if (kMore) stash_half((it + 1) & 1, 0);  // that stage was last read in iteration it-1
+    mfma_step(af1, bf1);  // k-step 1
+    interleave(kMore, 0);
+    load_frags(af1, bf1, a, b, 3);
+    if (kMore) stash_half((it + 1) & 1, 1);
+    mfma_step(af0, bf0);  // k-step 2
+    interleave(kMore, 0);
+    if (kMore) fetch(min(it + 2, nk - 1));  // the last iterations re-fetch the final tile: harmless, branch-free
+    mfma_step(af1, bf1);  // k-step 3
+    interleave(0, kMore);
+    if (kMore) __syncthreads();
+  };
+
   if (nk > 0) {
     fetch(0);
-    stash(0);
+    stash_half(0, 0);
+    stash_half(0, 1);
     __syncthreads();
     if (nk > 1) fetch(1);
-    for (int it = 0; it < nk; ++it) {
-      const unsigned char* a = lds + (it & 1) * kStageBytes;
-      const unsigned char* b = a + kOperandBytes;
-#pragma unroll
-      for (int s = 0; s < BK / 16; ++s) {
-        bf16x8 af[4], bf[4];
-#pragma unroll
-        for (int f = 0; f < 4; ++f) af[f] = read_frag<LA>(a, wm * 128 + f * 32, s, lane);
-#pragma unroll
-        for (int f = 0; f < 4; ++f) bf[f] = read_frag<LB>(b, wn * 128 + f * 32, s, lane);
-#pragma unroll
-        for (int fm = 0; fm < 4; ++fm)
-#pragma unroll
-          for (int fn = 0; fn < 4; ++fn)
-            acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[fn], af[fm], acc[fm][fn], 0, 0, 0);
-      }
-      if (it + 1 < nk) {
-        stash((it + 1) & 1);  // that stage was last read in iteration it-1; the barrier below closed it
-        __syncthreads();
-        if (it + 2 < nk) fetch(it + 2);
-      }
-    }
+    for (int it = 0; it < nk - 1; ++it) iteration(it, std::true_type{});
+    iteration(nk - 1, std::false_type{});
   }
 
   // ---- epilogue.  acc[fm][fn][4*rg + j] = C[row][col + j],
