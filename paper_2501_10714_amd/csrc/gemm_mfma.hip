@@ -1,14 +1,24 @@
 // bf16 grouped GEMM on the CDNA4 matrix cores for the expert FFNs (FSMoE Sec. 2.1 "Experts",
 // Sec. 4.4 for the backward products): the one dense contraction of the layer.
 //
-// One workgroup (256 lanes = 4 waves, one per SIMD) owns a 256x256 output tile and walks K in
-// steps of 64 through a two-stage LDS pipeline.  Each wave owns a 128x128 quadrant = 4x4 MFMA
-// 32x32x16 tiles, fp32 accumulators (256 registers per lane).
+// One workgroup (256 lanes = 4 waves, one per SIMD) owns a 256x256 output tile.  Each wave owns a
+// 128x128 quadrant = 4x4 MFMA 32x32x16 tiles, fp32 accumulators (256 registers per lane).
+//
+// K pipeline: four LDS stages of 32 k (16 KB per operand per stage, 128 KB in all).  Tiles travel
+// global -> LDS directly (global_load_lds_dwordx4, no registers, no ds_write); while stage i is
+// multiplied, stages i+1..i+3 are in flight, so about three stage-times of memory latency are
+// covered.  A wave-level load drops 64 x 16 bytes into 1 KB of contiguous LDS, so the bank swizzle
+// is applied on the global side: each lane fetches the chunk that belongs at its LDS slot.
+// The stages are separate __shared__ arrays and the K loop is unrolled by four, so every LDS access
+// names its stage statically; the compiler then knows a fragment read of one stage does not have to
+// wait for the loads that are filling another.
+// Fragments are double buffered across the barrier: the MFMAs of the second half of stage i-1 run
+// while the first fragments of stage i are read.
 //
 // Operand layouts in LDS (bf16):
-//   KC  "K-contiguous rows"  [256 rows][64 k]   128-byte rows, 16-byte chunks XOR-swizzled by row.
+//   KC  "K-contiguous rows"  [256 rows][32 k]   64-byte rows, 16-byte chunks XOR-swizzled by row.
 //        A lane reads its 8 consecutive k of one row with one ds_read_b128.
-//   TR  "transposed feed"    [64 k][256 cols]   512-byte rows, 32-byte segments XOR-swizzled by k.
+//   TR  "transposed feed"    [32 k][256 cols]   512-byte rows, 32-byte segments XOR-swizzled by k.
 //        The operand is N-contiguous in memory but the MFMA wants 8 consecutive k per lane:
 //        ds_read_b64_tr_b16 hands a 16-lane group the 4(k) x 16(col) block transposed.
 //   The three products need: forward  A=KC (activations), B=TR (W[k][n]);
@@ -33,26 +43,46 @@ namespace moe {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // native vector: stays in registers (HIP's uint4 struct copies as memcpy)
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // native vectors stay in registers
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef unsigned char __attribute__((address_space(3))) lds_byte;
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BM = 256, BN = 256, BK = 32;
 constexpr int kThreads = 256;
-constexpr int kOperandBytes = BM * BK * 2;      // 32 KB
-constexpr int kStageBytes = 2 * kOperandBytes;  // A | B
-constexpr int kLdsBytes = 2 * kStageBytes;      // two stages: 128 KB
-constexpr int kBand = 8;                        // row-tiles per L2 band
-constexpr int kSlots = 8;                       // 16-byte chunks per thread per operand per stage
+constexpr int kStages = 4;
+constexpr int kOpBytes = BM * BK * 2;  // 16 KB: one operand, one stage
+constexpr int kBand = 8;               // row-tiles per L2 band
+constexpr int kLoads = kOpBytes / 1024 / 4;  // wave-level 1 KB loads per wave per operand per stage (4)
 
 enum Layout { KC = 0, TR = 1 };
 
-__device__ __forceinline__ int kc_chunk_off(int row, int c) { return row * 128 + ((c ^ ((row >> 1) & 7)) << 4); }
-__device__ __forceinline__ int tr_chunk_off(int krow, int c) {  // c: 16-byte chunk (8 cols) of the 512-byte k-row
-  return krow * 512 + ((((c >> 1) ^ (krow & 15))) << 5) + ((c & 1) << 4);
+// One array per stage (A operand, then B operand): accesses name their stage statically (see the
+// header comment).  Four objects, so the compiler can track the in-flight loads of each separately.
+__shared__ __attribute__((aligned(1024))) unsigned char g_st0[2 * kOpBytes], g_st1[2 * kOpBytes], g_st2[2 * kOpBytes],
+    g_st3[2 * kOpBytes];
+
+template <int S> __device__ __forceinline__ unsigned char* stage_a() {
+  if constexpr (S == 0) return g_st0; else if constexpr (S == 1) return g_st1; else if constexpr (S == 2) return g_st2; else return g_st3;
 }
+template <int S> __device__ __forceinline__ unsigned char* stage_b() { return stage_a<S>() + kOpBytes; }
+
+// Direct global -> LDS load of 16 bytes per lane: lane i's data lands at lds_addr + 16 i (lds_addr
+// wave-uniform, goes through M0).  Issued as inline assembly so that the pipeline below, not the
+// compiler's conservative tracking of in-flight LDS writes, decides where the waits go.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const unsigned char* p) {
+  return (uint32_t)(uintptr_t)(lds_byte*)p;
+}
+__device__ __forceinline__ void stage_barrier() {
+  static_assert(2 * 2 * kLoads == 16, "the immediate below is vmcnt(16)");
+  asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+// ---- byte offset of a 16-byte chunk inside a stage
+__device__ __forceinline__ int kc_chunk_off(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
 
 // ---- fragment reads: 32 (rows or cols) x 16 k, as the MFMA 32x32x16 operand registers
 __device__ __forceinline__ bf16x8 read_kc(const unsigned char* op, int row0, int s, int lane) {
@@ -146,14 +176,14 @@ __device__ __forceinline__ TileId find_tile(const GemmP& p, int n_nt, int mt_fix
 
 template <int LA, int LB, int EPI, bool RAGGED_K, int ACT>
 __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt, int mt_fix) {
-  extern __shared__ __align__(16) unsigned char lds[];
   constexpr bool kGluFwd = EPI == EPI_GLU_FWD;
   constexpr int kOutCols = kGluFwd ? BN / 2 : BN;  // output columns per tile
 
   const TileId t = find_tile<RAGGED_K>(p, n_nt, mt_fix);
   if (!t.valid) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
   const int Kg = RAGGED_K ? t.rows : p.Kfix;
@@ -161,81 +191,98 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
   const int nk1 = (Kg + BK - 1) / BK;
   const int nk = nk1 * sum_pairs;
 
-  // ---- per-thread global chunk bookkeeping (element offsets from the operand base, k0 = 0)
-  const long lda = RAGGED_K ? p.sAk : p.sAi;  // row stride of the A array in memory
+  // ---- global side of the direct-to-LDS loads.  Load j of this wave fills the 1 KB block
+  //      blk = wave*4 + j of the stage; lane i owns bytes [16 i, 16 i + 16) of it and fetches the
+  //      chunk the swizzle puts there.  Pointers advance by a uniform stride per K stage.
+  const long lda = RAGGED_K ? p.sAk : p.sAi;  // row stride (elements) of the A array in memory
   const long ldb = RAGGED_K ? p.sBk : (LB == TR ? p.sBk : p.sBn);
-  long aoff[kSlots], boff[kSlots];
-  int alds[kSlots], blds[kSlots];
-  int bsrc[kSlots];  // which B matrix (GLU forward only)
-#pragma unroll
-  for (int r = 0; r < kSlots; ++r) {
-    const int q = tid + kThreads * r;
-    if (LA == KC) {  // rows = output rows of this expert, clamped to its last row
-      const int row = q >> 3, c = q & 7;
-      const int grow = t.r0 + min(t.mt * BM + row, t.rows - 1);
-      aoff[r] = (long)grow * lda + c * 8;
-      alds[r] = kc_chunk_off(row, c);
-    } else {  // ragged K: [k][i], i = output row (weight-gradient row), clamped to the matrix
-      const int krow = q >> 5, c = q & 31;
-      const int i0 = min(t.mt * BM + c * 8, p.Mfix - 8);
-      aoff[r] = (long)i0;  // row part added per step
-      alds[r] = tr_chunk_off(krow, c);
-    }
-    bsrc[r] = 0;
-    if (LB == KC) {  // rows = output columns n, k contiguous
-      const int row = q >> 3, c = q & 7;
-      const int n = min(t.nt * BN + row, p.N - 1);
-      boff[r] = (long)t.e * p.gB + (long)n * ldb + c * 8;
-      blds[r] = kc_chunk_off(row, c);
-    } else {
-      const int krow = q >> 5, c = q & 31;
-      int col;
-      if (kGluFwd) {  // tile columns: [wn][W1 64 | W3 64]
-        const int w = c >> 4, half = (c >> 3) & 1, nn = c & 7;
-        col = t.nt * kOutCols + w * 64 + nn * 8;
-        bsrc[r] = half;
-      } else {
-        col = t.nt * BN + c * 8;
-      }
-      col = min(col, p.N - 8);
-      boff[r] = (RAGGED_K ? 0 : (long)t.e * p.gB) + col;  // row part added per step
-      blds[r] = tr_chunk_off(krow, c);
-    }
-  }
-
-  u32x4 areg[kSlots], breg[kSlots];
-  auto fetch = [&](int it) {
-    const int pr = it / nk1;
-    const int k0 = (it - pr * nk1) * BK;
-    const bf16_t* A = static_cast<const bf16_t*>(p.A[RAGGED_K ? 0 : pr]);
-    const bf16_t* B0 = static_cast<const bf16_t*>(p.B[RAGGED_K ? t.set : pr]);
+  const unsigned char* ga[kLoads];
+  const unsigned char* gb[kLoads];
+  int ka[kLoads], kb[kLoads];  // k-row inside the stage of this lane's slot (TR layouts)
+  {
+    const bf16_t* A = static_cast<const bf16_t*>(p.A[0]);
+    const bf16_t* B0 = static_cast<const bf16_t*>(p.B[RAGGED_K ? t.set : 0]);
     const bf16_t* B1 = kGluFwd ? static_cast<const bf16_t*>(p.B[1]) : B0;
 #pragma unroll
-    for (int r = 0; r < kSlots; ++r) {
-      if (LA == KC) {
-        areg[r] = *reinterpret_cast<const u32x4*>(A + aoff[r] + k0);
-      } else {
-        const int k = k0 + ((tid + kThreads * r) >> 5);
-        areg[r] = k < Kg ? *reinterpret_cast<const u32x4*>(A + (long)(t.r0 + k) * lda + aoff[r]) : u32x4{0u, 0u, 0u, 0u};
+    for (int j = 0; j < kLoads; ++j) {
+      const int blk = wave * kLoads + j;
+      if (LA == KC) {  // 16 rows x 64 B per block; rows = output rows of this expert, clamped to its last row
+        const int row = blk * 16 + (lane >> 2), slot = lane & 3;
+        const int c = slot ^ ((row >> 2) & 3);
+        const int grow = t.r0 + min(t.mt * BM + row, t.rows - 1);
+        ga[j] = reinterpret_cast<const unsigned char*>(A + (long)grow * lda + c * 8);
+        ka[j] = 0;
+      } else {  // 2 k-rows x 512 B per block; ragged K: [k][i], i = weight-gradient row, clamped to the matrix
+        const int krow = blk * 2 + (lane >> 5), pos = lane & 31;
+        const int seg = (pos >> 1) ^ (krow & 15);
+        const int i0 = min(t.mt * BM + (seg * 2 + (pos & 1)) * 8, p.Mfix - 8);
+        ga[j] = reinterpret_cast<const unsigned char*>(A + (long)(t.r0 + krow) * lda + i0);
+        ka[j] = krow;
       }
-      if (LB == KC) {
-        breg[r] = *reinterpret_cast<const u32x4*>(B0 + boff[r] + k0);
+      if (LB == KC) {  // rows = output columns n, k contiguous
+        const int row = blk * 16 + (lane >> 2), slot = lane & 3;
+        const int c = slot ^ ((row >> 2) & 3);
+        const int n = min(t.nt * BN + row, p.N - 1);
+        gb[j] = reinterpret_cast<const unsigned char*>(B0 + (long)t.e * p.gB + (long)n * ldb + c * 8);
+        kb[j] = 0;
       } else {
-        int k = k0 + ((tid + kThreads * r) >> 5);
-        if (RAGGED_K) k = t.r0 + min(k, Kg - 1);
-        breg[r] = *reinterpret_cast<const u32x4*>((bsrc[r] ? B1 : B0) + (long)k * ldb + boff[r]);
+        const int krow = blk * 2 + (lane >> 5), pos = lane & 31;
+        const int seg = (pos >> 1) ^ (krow & 15);
+        const int cc = seg * 2 + (pos & 1);  // 8-column chunk of the tile
+        int col;
+        const bf16_t* B = B0;
+        if (kGluFwd) {  // tile columns: [wn][W1 64 | W3 64]
+          col = t.nt * kOutCols + (cc >> 4) * 64 + (cc & 7) * 8;
+          if ((cc >> 3) & 1) B = B1;
+        } else {
+          col = t.nt * BN + cc * 8;
+        }
+        col = min(col, p.N - 8);
+        const long rowpart = RAGGED_K ? (long)(t.r0 + krow) * ldb : (long)t.e * p.gB + (long)krow * ldb;
+        gb[j] = reinterpret_cast<const unsigned char*>(B + rowpart + col);
+        kb[j] = krow;
       }
+    }
+  }
+  const long a_step = (LA == KC ? (long)BK : (long)BK * lda) * 2;  // bytes per K stage
+  const long b_step = (LB == KC ? (long)BK : (long)BK * ldb) * 2;
+  // second operand pair of a summed product (dxe = da1.W1^T + da3.W3^T): jump of the pointers at it = nk1
+  const long a_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.A[1]) - reinterpret_cast<const unsigned char*>(p.A[0]) - nk1 * a_step : 0;
+  const long b_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.B[1]) - reinterpret_cast<const unsigned char*>(p.B[0]) - nk1 * b_step : 0;
+
+  // Loads of K stage `it_load` into LDS stage S, one (A, B) pair of wave-level loads per call; after
+  // the last pair the pointers step to the next K stage.  Stages past the end re-fetch the last one
+  // (never read), so the number of loads in flight is the same in every iteration.
+  int it_load = 0;
+  auto issue_pair = [&](auto stage_tag, int j) {
+    constexpr int S = decltype(stage_tag)::value;
+    const uint32_t da = lds_addr_of(stage_a<S>()) + (wave * kLoads + j) * 1024;
+    const uint32_t db = lds_addr_of(stage_b<S>()) + (wave * kLoads + j) * 1024;
+    if (RAGGED_K) {
+      // rows past the expert's last re-read its last row (finite data); the A rows are zeroed in
+      // LDS once they have landed (see iteration()), so those products vanish
+      const int k0 = it_load * BK;
+      const int over_a = max(0, k0 + ka[j] - (Kg - 1));
+      const int over_b = max(0, k0 + kb[j] - (Kg - 1));
+      dma16(ga[j] - (long)over_a * lda * 2, da);
+      dma16(gb[j] - (long)over_b * ldb * 2, db);
+    } else {
+      dma16(ga[j], da);
+      dma16(gb[j], db);
+    }
+    if (j == kLoads - 1) {
+      const bool last = it_load + 1 >= nk;
+      const bool jump = it_load + 1 == nk1 && sum_pairs == 2;
+      const long da_ = last ? 0 : a_step + (jump ? a_jump : 0);
+      const long db_ = last ? 0 : b_step + (jump ? b_jump : 0);
+#pragma unroll
+      for (int q = 0; q < kLoads; ++q) { ga[q] += da_; gb[q] += db_; }
+      it_load += last ? 0 : 1;
     }
   };
-  // half h of the prefetched tile -> LDS stage
-  auto stash_half = [&](int stage, int h) {
-    unsigned char* a = lds + stage * kStageBytes;
-    unsigned char* b = a + kOperandBytes;
+  auto issue = [&](auto stage_tag) {
 #pragma unroll
-    for (int r = h * (kSlots / 2); r < (h + 1) * (kSlots / 2); ++r) {
-      *reinterpret_cast<u32x4*>(a + alds[r]) = areg[r];
-      *reinterpret_cast<u32x4*>(b + blds[r]) = breg[r];
-    }
+    for (int j = 0; j < kLoads; ++j) issue_pair(stage_tag, j);
   };
 
   f32x16 acc[4][4];
@@ -246,6 +293,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+  bf16x8 ax[4], bx[4], ay[4], by[4];  // fragment sets X (first 16 k of a stage) and Y (second 16 k)
   auto load_frags = [&](bf16x8(&af)[4], bf16x8(&bf)[4], const unsigned char* a, const unsigned char* b, int s) {
 #pragma unroll
     for (int f = 0; f < 4; ++f) af[f] = read_frag<LA>(a, wm * 128 + f * 32, s, lane);
@@ -259,52 +307,71 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
       for (int fn = 0; fn < 4; ++fn)
         acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[fn], af[fm], acc[fm][fn], 0, 0, 0);
   };
-  // LDS reads of one k-step spread over the 16 MFMAs of the previous one
-  constexpr int kReads = (LA == KC ? 4 : 8) + (LB == KC ? 4 : 8);
-  auto interleave = [&](int ds_writes, int vmem) {
+  constexpr int kReads = (LA == KC ? 4 : 8) + (LB == KC ? 4 : 8);  // LDS reads per k-step
+  auto interleave = [&]() {  // spread one k-step's LDS reads over the 16 MFMAs that run above them
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, (kReads + 7) / 8, 0);  // DS reads
-      if (ds_writes) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // 1 DS write
-      if (vmem) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);       // 2 VMEM reads
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, (kReads + 7) / 8, 0);
     }
   };
 
-  // One K iteration on LDS stage `it & 1`.  While its 64 MFMAs run, the tile for iteration it+1
-  // (already in registers) goes to the other stage and the loads for iteration it+2 are issued.
-  // Straight-line code (no branches) so that the scheduler can interleave the four instruction kinds.
-  auto iteration = [&](int it, auto more_tag) {
-    constexpr bool kMore = decltype(more_tag)::value;
-    const unsigned char* a = lds + (it & 1) * kStageBytes;
-    const unsigned char* b = a + kOperandBytes;
-    bf16x8 af0[4], bf0[4], af1[4], bf1[4];
-    load_frags(af0, bf0, a, b, 0);
-    load_frags(af1, bf1, a, b, 1);
-    mfma_step(af0, bf0);  // k-step 0
-    interleave(0, 0);
-    load_frags(af0, bf0, a, b, 2);
-    if (kMore) stash_half((it + 1) & 1, 0);  // that stage was last read in iteration it-1
-    mfma_step(af1, bf1);  // k-step 1
-    interleave(kMore, 0);
-    load_frags(af1, bf1, a, b, 3);
-    if (kMore) stash_half((it + 1) & 1, 1);
-    mfma_step(af0, bf0);  // k-step 2
-    interleave(kMore, 0);
-    if (kMore) fetch(min(it + 2, nk - 1));  // the last iterations re-fetch the final tile: harmless, branch-free
-    mfma_step(af1, bf1);  // k-step 3
-    interleave(0, kMore);
-    if (kMore) __syncthreads();
+  int it_cur = 0;
+  // One K stage.  On entry set Y holds the second half of the previous stage (kFirst: nothing).
+  auto iteration = [&](auto stage_tag, auto first_tag) {
+    constexpr int S = decltype(stage_tag)::value;
+    constexpr bool kFirst = decltype(first_tag)::value;
+    // (a) all but the two youngest stages of this wave's loads have landed, so stage S is in LDS;
+    // (b) this wave's fragment reads of stage S-1 have returned; then the barrier makes both true for
+    // every wave.  A bare s_barrier, not __syncthreads(): the fence of the latter waits for ALL loads.
+    stage_barrier();
+    if (RAGGED_K) {
+      if (it_cur == nk - 1 && (Kg & (BK - 1)) != 0) {  // ragged K tail: zero the A rows past the expert's last
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j)
+          if (it_cur * BK + ka[j] >= Kg)
+            *reinterpret_cast<u32x4*>(stage_a<S>() + (wave * kLoads + j) * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+        __syncthreads();
+      }
+      ++it_cur;
+    }
+    // first half: the loads of stage S+3, the first fragments (X) of this stage and the MFMAs of the
+    // previous stage's second half (Y), interleaved by hand: the loads are assembly statements and the
+    // scheduler keeps everything else on its side of them
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      issue_pair(std::integral_constant<int, (S + 3) % kStages>{}, j);
+      ax[j] = read_frag<LA>(stage_a<S>(), wm * 128 + j * 32, 0, lane);
+      bx[j] = read_frag<LB>(stage_b<S>(), wn * 128 + j * 32, 0, lane);
+      if (!kFirst) {
+#pragma unroll
+        for (int fn = 0; fn < 4; ++fn)
+          acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[fn], ay[j], acc[j][fn], 0, 0, 0);
+      }
+    }
+    // second half: this stage's second fragments (Y) under the MFMAs of X
+    load_frags(ay, by, stage_a<S>(), stage_b<S>(), 1);
+    mfma_step(ax, bx);
+    interleave();
   };
 
   if (nk > 0) {
-    fetch(0);
-    stash_half(0, 0);
-    stash_half(0, 1);
-    __syncthreads();
-    if (nk > 1) fetch(1);
-    for (int it = 0; it < nk - 1; ++it) iteration(it, std::true_type{});
-    iteration(nk - 1, std::false_type{});
+    issue(std::integral_constant<int, 0>{});
+    issue(std::integral_constant<int, 1>{});
+    issue(std::integral_constant<int, 2>{});
+    iteration(std::integral_constant<int, 0>{}, std::true_type{});
+    int it = 1;
+    for (; it + 4 <= nk; it += 4) {
+      iteration(std::integral_constant<int, 1>{}, std::false_type{});
+      iteration(std::integral_constant<int, 2>{}, std::false_type{});
+      iteration(std::integral_constant<int, 3>{}, std::false_type{});
+      iteration(std::integral_constant<int, 0>{}, std::false_type{});
+    }
+    if (it < nk) iteration(std::integral_constant<int, 1>{}, std::false_type{});
+    if (it + 1 < nk) iteration(std::integral_constant<int, 2>{}, std::false_type{});
+    if (it + 2 < nk) iteration(std::integral_constant<int, 3>{}, std::false_type{});
+    mfma_step(ay, by);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end must land before the LDS goes back to the pool
   }
 
   // ---- epilogue.  acc[fm][fn][4*rg + j] = C[row][col + j],
@@ -382,19 +449,9 @@ moe_status_t launch_cfg(const GemmP& p, hipStream_t s) {
     max_tiles = (int)((rows_bound + BM - 1) / BM + p.n_experts) * n_nt;
   }
   if (max_tiles <= 0) return MOE_OK;
-  static bool attr_set = false;
   auto kern = gg_mfma_kernel<LA, LB, EPI, RAGGED_K, ACT>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kLdsBytes);
-    if (e != hipSuccess) {
-      set_error("hipFuncSetAttribute(max dynamic LDS %d): %s", kLdsBytes, hipGetErrorString(e));
-      return MOE_ERR_DEVICE;
-    }
-    attr_set = true;
-  }
   const int grid = ceil_div(max_tiles, 8) * 8;  // the XCD remap wants a multiple of 8
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, s, p, n_nt, mt_fix);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), 0, s, p, n_nt, mt_fix);
   MOE_CHECK_LAUNCH();
   return MOE_OK;
 }
