@@ -55,6 +55,8 @@ constexpr int kStages = 4;
 constexpr int kOpBytes = BM * BK * 2;  // 16 KB: one operand, one stage
 constexpr int kBand = 8;               // row-tiles per L2 band
 constexpr int kLoads = kOpBytes / 1024 / 4;  // wave-level 1 KB loads per wave per operand per stage (4)
+constexpr int kPartBytes = kLoads * 1024;    // one wave's share of one operand of one stage (4 KB)
+constexpr int kRegionBytes = 2 * kPartBytes; // a stage is four wave regions [A part | B part]
 
 enum Layout { KC = 0, TR = 1 };
 
@@ -66,13 +68,30 @@ __shared__ __attribute__((aligned(1024))) unsigned char g_st0[2 * kOpBytes], g_s
 template <int S> __device__ __forceinline__ unsigned char* stage_a() {
   if constexpr (S == 0) return g_st0; else if constexpr (S == 1) return g_st1; else if constexpr (S == 2) return g_st2; else return g_st3;
 }
-template <int S> __device__ __forceinline__ unsigned char* stage_b() { return stage_a<S>() + kOpBytes; }
+template <int S> __device__ __forceinline__ unsigned char* stage_b() { return stage_a<S>() + kPartBytes; }
 
-// Direct global -> LDS load of 16 bytes per lane: lane i's data lands at lds_addr + 16 i (lds_addr
-// wave-uniform, goes through M0).  Issued as inline assembly so that the pipeline below, not the
-// compiler's conservative tracking of in-flight LDS writes, decides where the waits go.
-__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+// Direct global -> LDS load of 16 bytes per lane: lane i's data lands at M0 + OFF + 16 i.  The
+// immediate offset is added to the global address as well, so callers pass the pointer minus OFF.
+// One M0 write serves a whole stage (a wave stalls on every M0 write until the loads issued before
+// it have left the queue): the wave's region of a stage is [A part | B part], M0 points between
+// the two and the eight loads use offsets -4096 .. 3072.
+// Issued as inline assembly so that the pipeline below, not the compiler's conservative tracking of
+// in-flight LDS writes, decides where the waits go.
+__device__ __forceinline__ void dma_set_base(uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" ::"s"(lds_addr) : "memory");
+}
+template <int OFF> __device__ __forceinline__ void dma16(const unsigned char* g) {
+  asm volatile("global_load_lds_dwordx4 %0, off offset:%1" ::"v"(g - OFF), "n"(OFF) : "memory");
+}
+// block j of the A part (j = 0..3) or of the B part
+template <bool IS_B> __device__ __forceinline__ void dma_block(const unsigned char* g, int j) {
+  constexpr int base = IS_B ? 0 : -kPartBytes;
+  switch (j) {
+    case 0: dma16<base>(g); break;
+    case 1: dma16<base + 1024>(g); break;
+    case 2: dma16<base + 2048>(g); break;
+    default: dma16<base + 3072>(g); break;
+  }
 }
 __device__ __forceinline__ uint32_t lds_addr_of(const unsigned char* p) {
   return (uint32_t)(uintptr_t)(lds_byte*)p;
@@ -82,7 +101,12 @@ __device__ __forceinline__ void stage_barrier() {
   asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 // ---- byte offset of a 16-byte chunk inside a stage
-__device__ __forceinline__ int kc_chunk_off(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
+// KC operand: row r of the tile lives in wave region r / 64
+__device__ __forceinline__ int kc_chunk_off(int row, int c) {
+  return (row >> 6) * kRegionBytes + (row & 63) * 64 + ((c ^ ((row >> 2) & 3)) << 4);
+}
+// TR operand: k-row k of the stage lives in wave region k / 8
+__device__ __forceinline__ int tr_row_off(int k) { return (k >> 3) * kRegionBytes + (k & 7) * 512; }
 
 // ---- fragment reads: 32 (rows or cols) x 16 k, as the MFMA 32x32x16 operand registers
 __device__ __forceinline__ bf16x8 read_kc(const unsigned char* op, int row0, int s, int lane) {
@@ -95,9 +119,9 @@ __device__ __forceinline__ bf16x8 read_tr(const unsigned char* op, int col0, int
   const int grp = lane >> 4, i = lane & 15;
   const int seg = (col0 >> 4) + (grp & 1);          // 16-column segment of the tile
   const int k = 16 * s + 8 * (grp >> 1) + (i >> 2);  // k-row this lane addresses for the first read
-  const int a0 = k * 512 + ((seg ^ (k & 15)) << 5) + ((i & 3) << 3);
+  const int a0 = tr_row_off(k) + ((seg ^ (k & 15)) << 5) + ((i & 3) << 3);
   const int k1 = k + 4;
-  const int a1 = k1 * 512 + ((seg ^ (k1 & 15)) << 5) + ((i & 3) << 3);
+  const int a1 = tr_row_off(k1) + ((seg ^ (k1 & 15)) << 5) + ((i & 3) << 3);
   typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(op + a0));
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(op + a1));
@@ -256,19 +280,18 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
   int it_load = 0;
   auto issue_pair = [&](auto stage_tag, int j) {
     constexpr int S = decltype(stage_tag)::value;
-    const uint32_t da = lds_addr_of(stage_a<S>()) + (wave * kLoads + j) * 1024;
-    const uint32_t db = lds_addr_of(stage_b<S>()) + (wave * kLoads + j) * 1024;
+    if (j == 0) dma_set_base(lds_addr_of(stage_a<S>()) + wave * kRegionBytes + kPartBytes);
     if (RAGGED_K) {
       // rows past the expert's last re-read its last row (finite data); the A rows are zeroed in
       // LDS once they have landed (see iteration()), so those products vanish
       const int k0 = it_load * BK;
       const int over_a = max(0, k0 + ka[j] - (Kg - 1));
       const int over_b = max(0, k0 + kb[j] - (Kg - 1));
-      dma16(ga[j] - (long)over_a * lda * 2, da);
-      dma16(gb[j] - (long)over_b * ldb * 2, db);
+      dma_block<false>(ga[j] - (long)over_a * lda * 2, j);
+      dma_block<true>(gb[j] - (long)over_b * ldb * 2, j);
     } else {
-      dma16(ga[j], da);
-      dma16(gb[j], db);
+      dma_block<false>(ga[j], j);
+      dma_block<true>(gb[j], j);
     }
     if (j == kLoads - 1) {
       const bool last = it_load + 1 >= nk;
@@ -308,12 +331,13 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[fn], af[fm], acc[fm][fn], 0, 0, 0);
   };
   constexpr int kReads = (LA == KC ? 4 : 8) + (LB == KC ? 4 : 8);  // LDS reads per k-step
-  auto interleave = [&]() {  // spread one k-step's LDS reads over the 16 MFMAs that run above them
+  auto interleave = [&]() {  // the k-step's LDS reads go out under the first MFMAs, so they are back at the barrier
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, (kReads + 7) / 8, 0);
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, (kReads + 3) / 4, 0);
     }
+    __builtin_amdgcn_sched_group_barrier(0x008, 12, 0);
   };
 
   int it_cur = 0;
@@ -330,7 +354,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
 #pragma unroll
         for (int j = 0; j < kLoads; ++j)
           if (it_cur * BK + ka[j] >= Kg)
-            *reinterpret_cast<u32x4*>(stage_a<S>() + (wave * kLoads + j) * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(stage_a<S>() + wave * kRegionBytes + j * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
         __syncthreads();
       }
       ++it_cur;
@@ -341,8 +365,14 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       issue_pair(std::integral_constant<int, (S + 3) % kStages>{}, j);
-      ax[j] = read_frag<LA>(stage_a<S>(), wm * 128 + j * 32, 0, lane);
-      bx[j] = read_frag<LB>(stage_b<S>(), wn * 128 + j * 32, 0, lane);
+      // B fragments first: the first MFMA on X needs all four of them, but only ax[0]
+      if (j < 2) {
+        bx[2 * j] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j) * 32, 0, lane);
+        bx[2 * j + 1] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j + 1) * 32, 0, lane);
+      } else {
+        ax[2 * j - 4] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 4) * 32, 0, lane);
+        ax[2 * j - 3] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 3) * 32, 0, lane);
+      }
       if (!kFirst) {
 #pragma unroll
         for (int fn = 0; fn < 4; ++fn)
