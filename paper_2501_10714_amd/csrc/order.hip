@@ -142,15 +142,17 @@ __global__ __launch_bounds__(kBlock) void combine_bwd_kernel(const T* __restrict
       dot[j] = v;
     }
   }
-  if (tpr > 64) {  // tpr == kBlock: the whole block serves one token
+  if (tpr > 64) {  // a row spans tpr / 64 waves: sum their partials in wave order
     const int wave = threadIdx.x >> 6;
+    const int wpr = tpr >> 6;
     if ((threadIdx.x & 63) == 0)
       for (int j = 0; j < top_k; ++j) red[j][wave] = dot[j];
     __syncthreads();
-    if (threadIdx.x < top_k && live) {
+    if (lane < top_k && live) {
+      const int first = (threadIdx.x / tpr) * wpr;
       float v = 0.0f;
-      for (int wv = 0; wv < kBlock / 64; ++wv) v += red[threadIdx.x][wv];
-      dtopk_w[(size_t)t * top_k + threadIdx.x] = v;  // dropped choices never accumulated: 0
+      for (int wv = 0; wv < wpr; ++wv) v += red[lane][first + wv];
+      dtopk_w[(size_t)t * top_k + lane] = v;  // dropped choices never accumulated: 0
     }
   } else if (live && lane == 0) {
 #pragma unroll

@@ -1,0 +1,95 @@
+"""GPU parity at the full benchmark shapes, through the fused layer calls in the configuration
+bench.py times.  The GPT-2 shape is checked against the full oracle.  The three larger shapes are
+checked on what the oracle can compute one by one: the routing in full (bit exact), y / dx / dtopk_w
+for a seeded sample of tokens, columns of every expert's weight gradients over all of its rows, and
+dW_g / db_g in full through a second backward pass whose dy is zero outside the sampled tokens."""
+import numpy as np
+import pytest
+import torch
+
+import moe_synth as S
+import paper_2501_10714_amd as moe
+from oracle import moe_oracle as O
+from moe_harness import (TOL, Buffers, assert_routing_equal, cap_of, dev_inputs, make_cfg, oracle_layer, rel_err,
+                         run_layer, saved_np, to_dev, to_np)
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+ROUTING = ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")
+
+
+def test_gpt2_shape_full_oracle():
+    w = S.WORKLOADS["gpt2"]
+    d = S.draw_all(w)
+    f, fwd, bwd = oracle_layer(w, d)
+    cfg, b = run_layer(w, d)
+    got = {n: saved_np(cfg, b, n, torch.int32).reshape(np.asarray(fwd[n]).shape) for n in ROUTING}
+    assert_routing_equal(got, fwd)
+    assert int(fwd["count"].max()) <= 1229     # balanced gate: the capacity is not reached at this shape
+    assert np.array_equal(saved_np(cfg, b, "logits", torch.float32).reshape(w.N, w.E), fwd["logits"].astype(np.float64))
+    tol = TOL[w.dtype]
+    for name, want in (("y", fwd["y"]), ("dx", bwd["dx"]), ("dw_gate", bwd["dw_gate"]), ("dw1", bwd["dw1"]),
+                       ("dw2", bwd["dw2"])):
+        assert rel_err(to_np(getattr(b, name)), want) <= tol, name
+
+
+@pytest.mark.parametrize("name", ["mixtral", "finegrained", "switch"])
+def test_large_shapes_sampled(name):
+    w = S.WORKLOADS[name]
+    d = S.draw_all(w)
+    tol = TOL[w.dtype]
+    x, dy, wg = S.to_f64(d["x"]), S.to_f64(d["dy"]), S.to_f64(d["w_gate"])
+    bg = None if d["b_gate"] is None else d["b_gate"].astype(np.float64)
+    cap = cap_of(w)
+    r = O.route(x, wg, bg, w.k, cap, w.renormalize)
+
+    dd = dev_inputs(d)
+    cfg, b = run_layer(w, d, dd=dd)
+    got = {n: saved_np(cfg, b, n, torch.int32).reshape(np.asarray(r[n]).shape) for n in ROUTING}
+    assert_routing_equal(got, r)
+    logits = saved_np(cfg, b, "logits", torch.float32).reshape(w.N, w.E)
+    assert np.array_equal(logits, r["logits"].astype(np.float64)), "gate logits differ in bits"
+    if w.f is None:
+        assert int(r["offsets"][-1]) == w.N * w.k            # f = *: nothing dropped
+    else:
+        assert int(r["count"].max()) <= cap and (r["pos"] < 0).any()
+
+    # ---- sampled tokens: y, dx, dtopk_w
+    toks = S.sample_indices(w, 192, w.N)
+    cache = {}
+
+    def expert_weight(which, e):
+        if (which, e) not in cache:
+            if len(cache) >= 3:
+                cache.clear()
+            cache[(which, e)] = S.to_f64(d[which][e])
+        return cache[(which, e)]
+
+    s = O.layer_tokens(toks, x, dy, wg, r, expert_weight, w.act, w.renormalize, w.add_residual, bg is not None)
+    assert rel_err(to_np(b.y[torch.from_numpy(toks).cuda()]), s["y"]) <= tol
+    assert rel_err(to_np(b.dx[torch.from_numpy(toks).cuda()]), s["dx"]) <= tol
+
+    # ---- weight-gradient columns over all rows of every (sampled) expert
+    experts = range(w.E) if w.E <= 8 else S.sample_indices(w, 8, w.E, part=1)
+    for e in experts:
+        cols = S.sample_indices(w, 12, w.H, part=100 + int(e))
+        c1, c3, c2 = O.expert_wgrad_columns(int(e), cols, x, dy, r, S.to_f64(d["w1"][e]),
+                                            S.to_f64(d["w3"][e]) if w.gated else None, S.to_f64(d["w2"][e]), w.act)
+        ct = torch.from_numpy(cols).cuda()
+        assert rel_err(to_np(b.dw1[e][:, ct]), c1) <= tol, ("dw1", e)
+        assert rel_err(to_np(b.dw2[e][ct, :]), c2) <= tol, ("dw2", e)
+        if w.gated:
+            assert rel_err(to_np(b.dw3[e][:, ct]), c3) <= tol, ("dw3", e)
+
+    # ---- gate gradients in full: backward with dy zero outside the sampled tokens
+    dy_m = np.zeros_like(d["dy"])
+    dy_m[toks] = d["dy"][toks]
+    dd["dy"] = to_dev(dy_m)
+    moe.moe_layer_bwd(cfg, dd["dy"], dd["x"], dd["w_gate"], dd["w1"], dd["w3"], dd["w2"], b.saved, b.dx, b.dw_gate,
+                      b.db_gate if bg is not None else None, b.dw1, b.dw3, b.dw2, b.ws)
+    torch.cuda.synchronize()
+    dl = s["dlogits"]                                        # rows of the sampled tokens; zero elsewhere
+    assert rel_err(to_np(b.dw_gate), x[toks].T @ dl) <= tol
+    if bg is not None:
+        assert rel_err(to_np(b.db_gate), dl.sum(0)) <= tol
+    others = np.setdiff1d(np.arange(w.N), toks)[:4096]
+    assert torch.count_nonzero(b.dx[torch.from_numpy(others).cuda()]).item() == 0   # no gradient without dy

@@ -29,6 +29,11 @@ CASES = {
     "fine_small": S.scaled(W["finegrained"], N=700, M=128, H=136, E=16, k=6, seed=23),  # H%64 != 0: plain GEMM for K=H
     "switch_small": S.scaled(W["switch"], N=2000, M=128, H=256, E=8, seed=24),    # top-1, f=1, residual, Zipf bias
     "erf_odd": S.scaled(W["gpt2"], N=130, M=72, H=88, E=3, k=3, act=S.ACT_GELU_ERF, seed=25),  # nothing tile aligned
+    # row movers: a token row spanning 2 waves (80 16-byte chunks), a whole block, and more than a block
+    "rows_2waves": S.scaled(W["gpt2"], N=300, M=640, H=64, E=4, seed=26),
+    "rows_block": S.scaled(W["mixtral"], N=200, M=2048, H=64, E=4, seed=27),
+    "rows_loop": S.scaled(W["switch"], N=150, M=2304, H=64, E=4, seed=28),
+    "rows_2waves_f32": S.scaled(W["tiny"], N=200, M=320, H=64, E=4, k=2, seed=29),
 }
 
 
