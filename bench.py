@@ -22,6 +22,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM bytes per step of the six expert-GEMM launches at the Mixtral shape, from the rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gg_mfma_kernel_mixtral_hbm_traffic.md (scaled by
+# the factors a plain 1 GiB copy gives: 2.0 and 1.0).  Algorithmic bytes for the same launches: 22.3e9.
+MEASURED_GEMM_TRAFFIC = {"mixtral": {"read": 68.2e9, "written": 11.8e9}}
 
 
 def parse():
@@ -32,6 +36,8 @@ def parse():
     ap.add_argument("--workload", default="mixtral", choices=["tiny", "gpt2", "mixtral", "finegrained", "switch"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -86,6 +92,12 @@ def main():
         moe.moe_layer_bwd(cfg, d["dy"], d["x"], d["w_gate"], d["w1"], d["w3"], d["w2"], b.saved, b.dx, b.dw_gate,
                           b.db_gate if has_bias else None, b.dw1, b.dw3, b.dw2, b.ws)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                   # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         fwd(); bwd()
     torch.cuda.synchronize()
@@ -128,7 +140,8 @@ def main():
     achieved = (flop_fwd + flop_bwd) / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gg_mfma_kernel (bf16 grouped GEMM, 2 forward + 4 backward launches per step)",
                 "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": (lambda t: None if t is None else t["read"] + t["written"])(MEASURED_GEMM_TRAFFIC.get(w.name)),
                 "flop_per_step": flop_fwd + flop_bwd, "ms_per_step": round(gemm_ms, 3),
                 "fwd": {"ms": round(t_ffn_fwd, 3), "tflops": round(flop_fwd / t_ffn_fwd / 1e9, 1)},
                 "bwd": {"ms": round(t_ffn_bwd, 3), "tflops": round(flop_bwd / t_ffn_bwd / 1e9, 1)}}
