@@ -26,8 +26,8 @@
 //                            wgrad    A=TR, B=TR (both operands are indexed by the ragged expert row).
 //
 // MFMA is issued with the operands swapped (B fragment first), so a lane ends up with 4 consecutive
-// output COLUMNS of one output row per accumulator quad: 8-byte bf16 stores and 8-byte loads of the
-// saved activations in the fused epilogues.
+// output COLUMNS of one output row per accumulator quad; the epilogue turns the quadrant row-major
+// through LDS so that global stores (and the loads of the saved activations) are full cache lines.
 //
 // Tile order: hardware deals workgroup ids round-robin to the 8 XCDs (each with its own L2), so
 // id -> (xcd, slot) is remapped to give every XCD a contiguous range of logical tiles; inside that
@@ -45,8 +45,8 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // native vectors stay in registers
-typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 typedef unsigned char __attribute__((address_space(3))) lds_byte;
 
 constexpr int BM = 256, BN = 256, BK = 32;
@@ -140,13 +140,16 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
   v.h[0] = (__bf16)a; v.h[1] = (__bf16)b;
   return v.u;
 }
-__device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, float d) {
-  *reinterpret_cast<u32x2*>(p) = u32x2{pack2(a, b), pack2(c, d)};
+__device__ __forceinline__ void store8(bf16_t* p, const float* v) {
+  *reinterpret_cast<u32x4*>(p) = u32x4{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])};
 }
-__device__ __forceinline__ void load4(const bf16_t* p, float* v) {
-  u32x2 r = *reinterpret_cast<const u32x2*>(p);
-  v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xFFFF0000u);
-  v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xFFFF0000u);
+__device__ __forceinline__ void load8(const bf16_t* p, float* v) {
+  const u32x4 r = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(r[i] << 16);
+    v[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
+  }
 }
 
 struct TileId {
@@ -404,61 +407,89 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end must land before the LDS goes back to the pool
   }
 
-  // ---- epilogue.  acc[fm][fn][4*rg + j] = C[row][col + j],
-  //      row = wm*128 + fm*32 + lane%32,  col = wn*128 + fn*32 + rg*8 + (lane/32)*4  (tile coordinates)
-  const int lrow = lane & 31, lcol = (lane >> 5) * 4;
+  // ---- epilogue.  In the accumulators a lane holds 4 consecutive columns of 32 different rows
+  // (acc[fm][fn][4 rg + j] = C[wm*128 + fm*32 + lane%32][wn*128 + fn*32 + rg*8 + (lane/32)*4 + j]);
+  // stored like that, every store instruction would scatter 16-byte pieces over 32 rows and the L2
+  // write path would set the pace.  Each wave therefore passes its quadrant through its own 32 KB of
+  // the (now idle) LDS, 32 rows at a time in fp32, and reads it back row-major: a lane then owns 8
+  // consecutive columns, 16 lanes cover 256 contiguous bytes of a row, and all global loads and
+  // stores of the fused epilogues are 16-byte vectors on full cache lines.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end have landed
+  __syncthreads();                                  // every wave is done with the K stages
+  float* scr = reinterpret_cast<float*>(wave == 0 ? g_st0 : wave == 1 ? g_st1 : wave == 2 ? g_st2 : g_st3);
+  constexpr int kPitch = 128 + 4;  // floats per scratch row (+16 bytes: conflict-free 16-byte column writes)
   const int m_limit = RAGGED_K ? p.Mfix : t.rows;
+  constexpr int kLanesPerRow = kGluFwd ? 8 : 16;   // 8 columns per lane
+  constexpr int kRowsPerPass = 64 / kLanesPerRow;
+  const int pr = lane / kLanesPerRow, c8 = (lane % kLanesPerRow) * 8;
+  const int col = kGluFwd ? t.nt * kOutCols + wn * 64 + c8 : t.nt * BN + wn * 128 + c8;
+  const bool col_ok = col < p.N;  // N is a multiple of 8
 #pragma unroll
   for (int fm = 0; fm < 4; ++fm) {
-    const int mrow = t.mt * BM + wm * 128 + fm * 32 + lrow;  // row inside the group
-    if (mrow >= m_limit) continue;
-    const long rbase = RAGGED_K ? (long)t.e * p.gC + (long)mrow * p.ldc : (long)(t.r0 + mrow) * p.ldc;
 #pragma unroll
-    for (int fn = 0; fn < (kGluFwd ? 2 : 4); ++fn) {
+    for (int fn = 0; fn < 4; ++fn)
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
-        const int col = kGluFwd ? t.nt * kOutCols + wn * 64 + fn * 32 + rg * 8 + lcol
-                                : t.nt * BN + wn * 128 + fn * 32 + rg * 8 + lcol;
-        if (col >= p.N) continue;
-        const long off = rbase + col;
-        float v[4];
+        f32x4 v = {acc[fm][fn][4 * rg], acc[fm][fn][4 * rg + 1], acc[fm][fn][4 * rg + 2], acc[fm][fn][4 * rg + 3]};
+        *reinterpret_cast<f32x4*>(scr + (lane & 31) * kPitch + fn * 32 + rg * 8 + (lane >> 5) * 4) = v;
+      }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = acc[fm][fn][4 * rg + j];
-        if (EPI == EPI_PLAIN) {
-          bf16_t* c = static_cast<bf16_t*>(p.C[RAGGED_K ? t.set : 0]) + off;
-          if (p.accumulate) {
-            float old[4];
-            load4(c, old);
+    for (int ps = 0; ps < 32 / kRowsPerPass; ++ps) {
+      const int r = ps * kRowsPerPass + pr;
+      const int mrow = t.mt * BM + wm * 128 + fm * 32 + r;  // row inside the group
+      float v[8];
+      {
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr + r * kPitch + c8);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr + r * kPitch + c8 + 4);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] += old[j];
-          }
-          store4(c, v[0], v[1], v[2], v[3]);
-        } else if (EPI == EPI_ACT_FWD) {
-          store4(static_cast<bf16_t*>(p.C[0]) + off, v[0], v[1], v[2], v[3]);
-          store4(static_cast<bf16_t*>(p.C[2]) + off, act_fwd(v[0], ACT), act_fwd(v[1], ACT), act_fwd(v[2], ACT),
-                 act_fwd(v[3], ACT));
-        } else if (EPI == EPI_GLU_FWD) {
-          float g[4];
+        for (int j = 0; j < 4; ++j) { v[j] = lo[j]; v[4 + j] = hi[j]; }
+      }
+      float g[8];
+      if (kGluFwd) {
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr + r * kPitch + 64 + c8);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr + r * kPitch + 64 + c8 + 4);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) g[j] = acc[fm][fn + 2][4 * rg + j];
-          store4(static_cast<bf16_t*>(p.C[0]) + off, v[0], v[1], v[2], v[3]);
-          store4(static_cast<bf16_t*>(p.C[1]) + off, g[0], g[1], g[2], g[3]);
-          store4(static_cast<bf16_t*>(p.C[2]) + off, siluf_(v[0]) * g[0], siluf_(v[1]) * g[1], siluf_(v[2]) * g[2],
-                 siluf_(v[3]) * g[3]);
-        } else if (EPI == EPI_ACT_BWD) {
-          float a1[4];
-          load4(static_cast<const bf16_t*>(p.X[0]) + off, a1);
-          store4(static_cast<bf16_t*>(p.C[0]) + off, v[0] * act_grad(a1[0], ACT), v[1] * act_grad(a1[1], ACT),
-                 v[2] * act_grad(a1[2], ACT), v[3] * act_grad(a1[3], ACT));
-        } else {
-          float a1[4], a3[4];
-          load4(static_cast<const bf16_t*>(p.X[0]) + off, a1);
-          load4(static_cast<const bf16_t*>(p.X[1]) + off, a3);
-          store4(static_cast<bf16_t*>(p.C[0]) + off, v[0] * a3[0] * silu_gradf_(a1[0]), v[1] * a3[1] * silu_gradf_(a1[1]),
-                 v[2] * a3[2] * silu_gradf_(a1[2]), v[3] * a3[3] * silu_gradf_(a1[3]));
-          store4(static_cast<bf16_t*>(p.C[1]) + off, v[0] * siluf_(a1[0]), v[1] * siluf_(a1[1]), v[2] * siluf_(a1[2]),
-                 v[3] * siluf_(a1[3]));
+        for (int j = 0; j < 4; ++j) { g[j] = lo[j]; g[4 + j] = hi[j]; }
+      }
+      if (mrow >= m_limit || !col_ok) continue;
+      const long off = (RAGGED_K ? (long)t.e * p.gC + (long)mrow * p.ldc : (long)(t.r0 + mrow) * p.ldc) + col;
+      if (EPI == EPI_PLAIN) {
+        bf16_t* c = static_cast<bf16_t*>(p.C[RAGGED_K ? t.set : 0]) + off;
+        if (p.accumulate) {
+          float old[8];
+          load8(c, old);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) v[j] += old[j];
         }
+        store8(c, v);
+      } else if (EPI == EPI_ACT_FWD) {
+        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = act_fwd(v[j], ACT);
+        store8(static_cast<bf16_t*>(p.C[2]) + off, v);
+      } else if (EPI == EPI_GLU_FWD) {
+        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
+        store8(static_cast<bf16_t*>(p.C[1]) + off, g);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = siluf_(v[j]) * g[j];
+        store8(static_cast<bf16_t*>(p.C[2]) + off, v);
+      } else if (EPI == EPI_ACT_BWD) {
+        float a1[8];
+        load8(static_cast<const bf16_t*>(p.X[0]) + off, a1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] *= act_grad(a1[j], ACT);
+        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
+      } else {
+        float a1[8], a3[8], d1[8], d3[8];
+        load8(static_cast<const bf16_t*>(p.X[0]) + off, a1);
+        load8(static_cast<const bf16_t*>(p.X[1]) + off, a3);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          d1[j] = v[j] * a3[j] * silu_gradf_(a1[j]);
+          d3[j] = v[j] * siluf_(a1[j]);
+        }
+        store8(static_cast<bf16_t*>(p.C[0]) + off, d1);
+        store8(static_cast<bf16_t*>(p.C[1]) + off, d3);
       }
     }
   }
