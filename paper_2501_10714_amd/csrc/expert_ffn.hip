@@ -15,10 +15,6 @@
 
 namespace moe {
 
-moe_status_t launch_gemm_plain(const GemmP& p, int dtype, int epi, bool ragged_k, hipStream_t s);
-bool gemm_mfma_supported(const GemmP& p, int dtype, int epi, bool ragged_k);
-moe_status_t launch_gemm_mfma(const GemmP& p, int epi, bool ragged_k, hipStream_t s);
-
 namespace {
 
 // MOE_FORCE_PLAIN_GEMM=1 routes every product through the plain FMA kernel (for A/B checks of the MFMA path)

@@ -1,7 +1,10 @@
 // Description of one grouped (per-expert) GEMM launch of the expert FFN (FSMoE Sec. 2.1 "Experts",
 // Sec. 4.4 for the backward products).  Shared by the plain fp32-FMA kernel and the bf16 MFMA kernel.
 #pragma once
+#include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "../../include/moe_mi355x.h"
 
 namespace moe {
 
@@ -36,5 +39,10 @@ struct GemmP {
   int max_rows;            // upper bound on rows per expert known on the host
   long total_rows_bound;   // upper bound on A = offsets[E] known on the host (N*k)
 };
+
+// gemm_mfma.hip / gemm_plain.hip
+bool gemm_mfma_supported(const GemmP& p, int dtype, int epi, bool ragged_k);
+moe_status_t launch_gemm_mfma(const GemmP& p, int epi, bool ragged_k, hipStream_t s);
+moe_status_t launch_gemm_plain(const GemmP& p, int dtype, int epi, bool ragged_k, hipStream_t s);
 
 }  // namespace moe

@@ -17,6 +17,7 @@
 // the fp64 copy and feeds v_fma_f64 as a scalar operand.  x goes through LDS (coalesced 16-byte
 // global loads, row reads by the owning lane).
 #include "common.h"
+#include "gemm_params.h"
 
 namespace moe {
 namespace {
@@ -360,18 +361,29 @@ constexpr int kDwThreads = 128;
 constexpr int kDxTokens = 16;    // tokens per block of the dx update
 constexpr int kEc = 8;           // experts per register chunk
 
+constexpr int kSplitTokens = 512;  // tokens per split-K group of the bf16 dW_g product
+
 struct RouteBwdPlan {
-  int ntile;
-  size_t off_dl, off_part, off_bpart, bytes;
+  int ntile;   // 256-token tiles (fp32 path partial sums, and the db_g column sums of both paths)
+  int ep;      // experts padded to a multiple of 32 (bf16 path: K of the dx product, N of the dW_g product)
+  int nsplit;  // split-K groups of the bf16 dW_g product
+  size_t off_dl, off_part, off_bpart, off_dlb, off_wgp, off_tok, bytes;
 };
 
 RouteBwdPlan route_bwd_plan(const moe_config_t& c) {
   RouteBwdPlan p;
+  const bool bf = c.dtype == MOE_BF16;
   p.ntile = ceil_div(c.n_tokens, kDwTokens);
+  p.ep = ceil_div(c.n_experts, 32) * 32;
+  p.nsplit = ceil_div(c.n_tokens, kSplitTokens);
   size_t o = 0;
   p.off_dl = o; o += align_up((size_t)c.n_tokens * c.n_experts * sizeof(float), 256);
-  p.off_part = o; o += align_up((size_t)p.ntile * c.d_model * c.n_experts * sizeof(float), 256);
+  p.off_part = o;  // fp32 path: [ntile][M][E] f32; bf16 path: [nsplit][M][ep] bf16
+  o += align_up(bf ? (size_t)p.nsplit * c.d_model * p.ep * 2 : (size_t)p.ntile * c.d_model * c.n_experts * sizeof(float), 256);
   p.off_bpart = o; o += align_up((size_t)p.ntile * c.n_experts * sizeof(float), 256);
+  p.off_dlb = o; o += bf ? align_up((size_t)c.n_tokens * p.ep * 2, 256) : 0;
+  p.off_wgp = o; o += bf ? align_up((size_t)c.d_model * p.ep * 2, 256) : 0;
+  p.off_tok = o; o += bf ? align_up((size_t)(p.nsplit + 3) * sizeof(int32_t), 256) : 0;
   p.bytes = o;
   return p;
 }
@@ -381,21 +393,61 @@ __global__ __launch_bounds__(256) void dlogits_kernel(const float* __restrict__ 
                                                       const int32_t* __restrict__ topk_idx,
                                                       const int32_t* __restrict__ pos,
                                                       const float* __restrict__ dtopk_w, float* __restrict__ dl,
-                                                      int n_tokens, int n_experts, int top_k) {
+                                                      bf16_t* __restrict__ dlb, int n_tokens, int n_experts,
+                                                      int top_k, int ep) {
+  // one thread per (token, padded expert); dlb (optional) is the bf16 copy with zero columns up to ep
+  const int width = dlb != nullptr ? ep : n_experts;
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= (size_t)n_tokens * n_experts) return;
-  const int t = (int)(i / n_experts), e = (int)(i % n_experts);
-  float s = 0.0f, g = 0.0f;
-  for (int j = 0; j < top_k; ++j) {
-    const size_t a = (size_t)t * top_k + j;
-    if (pos[a] >= 0) {
-      const int ej = topk_idx[a];
-      const float d = dtopk_w[a];
-      s = fmaf(d, probs[(size_t)t * n_experts + ej], s);
-      if (ej == e) g = d;
+  if (i >= (size_t)n_tokens * width) return;
+  const int t = (int)(i / width), e = (int)(i % width);
+  float v = 0.0f;
+  if (e < n_experts) {
+    float s = 0.0f, g = 0.0f;
+    for (int j = 0; j < top_k; ++j) {
+      const size_t a = (size_t)t * top_k + j;
+      if (pos[a] >= 0) {
+        const int ej = topk_idx[a];
+        const float d = dtopk_w[a];
+        s = fmaf(d, probs[(size_t)t * n_experts + ej], s);
+        if (ej == e) g = d;
+      }
     }
+    v = probs[(size_t)t * n_experts + e] * (g - s);
+    dl[(size_t)t * n_experts + e] = v;
   }
-  dl[i] = probs[i] * (g - s);
+  if (dlb != nullptr) dlb[i] = f32_to_bf16(v);
+}
+
+// bf16 path helpers: W_g with zero columns up to ep, and the row ranges of the two grouped products
+__global__ void pad_gate_kernel(const bf16_t* __restrict__ w_gate, bf16_t* __restrict__ wgp, int32_t* __restrict__ tok,
+                                int d_model, int n_experts, int ep, int n_tokens, int nsplit) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < d_model * ep) {
+    const int m = i / ep, e = i % ep;
+    wgp[i] = e < n_experts ? w_gate[(size_t)m * n_experts + e] : (bf16_t)0;
+  }
+  // tok[0..nsplit] = split-K token ranges; tok[nsplit+1 .. nsplit+2] = {0, N}: the single group of the dx product
+  if (i <= nsplit) tok[i] = min(i * kSplitTokens, n_tokens);
+  if (i == 0) { tok[nsplit + 1] = 0; tok[nsplit + 2] = n_tokens; }
+}
+
+__global__ __launch_bounds__(256) void gate_dw_reduce_bf16_kernel(const bf16_t* __restrict__ part,
+                                                                  const float* __restrict__ bpart,
+                                                                  bf16_t* __restrict__ dw_gate,
+                                                                  float* __restrict__ db_gate, int nsplit, int ntile,
+                                                                  int d_model, int n_experts, int ep) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < d_model * n_experts) {
+    const int m = i / n_experts, e = i % n_experts;
+    float s = 0.0f;
+    for (int g = 0; g < nsplit; ++g) s += bf16_to_f32(part[((size_t)g * d_model + m) * ep + e]);
+    dw_gate[i] = f32_to_bf16(s);
+  }
+  if (db_gate != nullptr && i < n_experts) {
+    float s = 0.0f;
+    for (int tl = 0; tl < ntile; ++tl) s += bpart[(size_t)tl * n_experts + i];
+    db_gate[i] = s;
+  }
 }
 
 // dx[t, m..m+V) += sum_e dl[t,e] * W_g[m.., e]; a thread owns one 16-byte column chunk for kDxTokens tokens
@@ -526,10 +578,11 @@ __global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __rest
   }
 }
 
-template <typename T>
-moe_status_t route_bwd_t(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
-                         const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
-                         float* db_gate, void* dx, void* ws, hipStream_t s) {
+// fp32: plain FMA kernels.  dW_g through per-256-token partial sums reduced in tile order.
+moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
+                           const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                           float* db_gate, void* dx, void* ws, hipStream_t s) {
+  typedef float T;
   constexpr int V = Elem<T>::kVec;
   RouteBwdPlan p = route_bwd_plan(c);
   unsigned char* w = static_cast<unsigned char*>(ws);
@@ -538,7 +591,7 @@ moe_status_t route_bwd_t(const moe_config_t& c, const void* x, const void* w_gat
   float* bpart = reinterpret_cast<float*>(w + p.off_bpart);
   const size_t ne = (size_t)c.n_tokens * c.n_experts;
   hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
-                     dl, c.n_tokens, c.n_experts, c.top_k);
+                     dl, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0);
   MOE_CHECK_LAUNCH();
   hipLaunchKernelGGL(gate_dx_kernel<T>, dim3(ceil_div(c.n_tokens, kDxTokens), ceil_div(c.d_model, 256 * V)), dim3(256),
                      (size_t)kDxTokens * c.n_experts * sizeof(float), s, dl, (const T*)w_gate, (T*)dx, c.n_tokens,
@@ -554,6 +607,60 @@ moe_status_t route_bwd_t(const moe_config_t& c, const void* x, const void* w_gat
   }
   hipLaunchKernelGGL(gate_dw_reduce_kernel<T>, dim3(ceil_div(c.d_model * c.n_experts, 256)), dim3(256), 0, s, part, bpart,
                      (T*)dw_gate, db_gate, p.ntile, c.d_model, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
+}
+
+// bf16: both products go through the MFMA grouped GEMM with dlogits rounded to bf16 (E padded to a
+// multiple of 32 with zero columns):
+//   dx += dl.W_g^T   one group of N rows, K = ep, accumulate epilogue          (HBM-bound: dx read + written)
+//   dW_g = x^T.dl    split-K groups of 512 tokens, bf16 partials summed in group order   (HBM-bound: x read)
+moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
+                            const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                            float* db_gate, void* dx, void* ws, hipStream_t s) {
+  RouteBwdPlan p = route_bwd_plan(c);
+  unsigned char* w = static_cast<unsigned char*>(ws);
+  float* dl = reinterpret_cast<float*>(w + p.off_dl);
+  bf16_t* part = reinterpret_cast<bf16_t*>(w + p.off_part);
+  float* bpart = reinterpret_cast<float*>(w + p.off_bpart);
+  bf16_t* dlb = reinterpret_cast<bf16_t*>(w + p.off_dlb);
+  bf16_t* wgp = reinterpret_cast<bf16_t*>(w + p.off_wgp);
+  int32_t* tok = reinterpret_cast<int32_t*>(w + p.off_tok);
+  const size_t ne = (size_t)c.n_tokens * p.ep;
+  hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
+                     dl, dlb, c.n_tokens, c.n_experts, c.top_k, p.ep);
+  MOE_CHECK_LAUNCH();
+  const int npad = c.d_model * p.ep > p.nsplit + 1 ? c.d_model * p.ep : p.nsplit + 1;
+  hipLaunchKernelGGL(pad_gate_kernel, dim3(ceil_div(npad, 256)), dim3(256), 0, s, (const bf16_t*)w_gate, wgp, tok,
+                     c.d_model, c.n_experts, p.ep, c.n_tokens, p.nsplit);
+  MOE_CHECK_LAUNCH();
+  {  // dx += dlb.wgp^T : [N,ep] x [ep,M], B(k=e, n=m) = wgp[m][e]
+    GemmP g = {};
+    g.offsets = tok + p.nsplit + 1; g.n_experts = 1; g.n_pairs = 1;
+    g.A[0] = dlb; g.sAi = p.ep; g.sAk = 1;
+    g.B[0] = wgp; g.sBk = 1; g.sBn = p.ep; g.gB = 0;
+    g.C[0] = dx; g.ldc = c.d_model; g.N = c.d_model; g.Kfix = p.ep;
+    g.accumulate = 1; g.max_rows = c.n_tokens; g.total_rows_bound = c.n_tokens;
+    moe_status_t st = launch_gemm_mfma(g, EPI_PLAIN, false, s);
+    if (st != MOE_OK) return st;
+  }
+  {  // part[g] = x_g^T.dlb_g : [M,rows] x [rows,ep] for every 512-token group
+    GemmP g = {};
+    g.offsets = tok; g.n_experts = p.nsplit; g.n_pairs = 1;
+    g.A[0] = x; g.sAi = 1; g.sAk = c.d_model;
+    g.B[0] = dlb; g.sBk = p.ep; g.sBn = 1;
+    g.C[0] = part; g.ldc = p.ep; g.gC = (long)c.d_model * p.ep;
+    g.Mfix = c.d_model; g.N = p.ep;
+    g.max_rows = kSplitTokens; g.total_rows_bound = c.n_tokens;
+    moe_status_t st = launch_gemm_mfma(g, EPI_PLAIN, true, s);
+    if (st != MOE_OK) return st;
+  }
+  if (db_gate != nullptr) {
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3(p.ntile), dim3(256), 0, s, dl, bpart, c.n_tokens, c.n_experts);
+    MOE_CHECK_LAUNCH();
+  }
+  hipLaunchKernelGGL(gate_dw_reduce_bf16_kernel, dim3(ceil_div(c.d_model * c.n_experts, 256)), dim3(256), 0, s, part,
+                     bpart, (bf16_t*)dw_gate, db_gate, p.nsplit, p.ntile, c.d_model, c.n_experts, p.ep);
   MOE_CHECK_LAUNCH();
   return MOE_OK;
 }
@@ -576,8 +683,8 @@ moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* 
                               const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                               float* db_gate, void* dx, void* ws, hipStream_t s) {
   return c.dtype == MOE_BF16
-             ? route_bwd_t<bf16_t>(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s)
-             : route_bwd_t<float>(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s);
+             ? route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s)
+             : route_bwd_f32(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s);
 }
 
 }  // namespace moe
