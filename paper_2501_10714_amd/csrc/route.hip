@@ -12,27 +12,23 @@
 // Positions come from prefix sums only (no atomics decide an index), so the result is the same on
 // every run and equals the serial walk "for j, for t".
 //
-// The logits kernel keeps one token per lane and splits K = d_model over the block's eight waves,
-// so the W_g row a wave needs is the same for all its lanes: it is read through scalar loads from
-// the fp64 copy and feeds v_fma_f64 as a scalar operand.  x goes through LDS (coalesced 16-byte
-// global loads, row reads by the owning lane).
+// The logits are an fp64 GEMM on the vector ALU (register tiled, operands through LDS): the price of
+// routing that matches an independent oracle bit for bit whatever the summation order.
 #include "common.h"
 #include "gemm_params.h"
 
 namespace moe {
 namespace {
 
-constexpr int kTile = 64;          // tokens per block (one per lane)
-constexpr int kGateThreads = 512;  // 8 waves split K
-constexpr int kWaves = kGateThreads / 64;
-constexpr int kRowBytes = 512;     // bytes of one token row staged per K chunk
-constexpr int kRowStride = kRowBytes + 16;
+constexpr int kTile = 64;          // tokens per block
+constexpr int kGateThreads = 256;
+constexpr int kKC = 64;            // k per staged chunk
+constexpr int kXP = kTile + 2;     // pitch (doubles) of a k-row of the staged x chunk
 constexpr int kMaxK = 8;
 
 struct RoutePlan {
-  int ee;      // experts per register chunk (8,16,32,64)
+  int ee;      // experts per pass (8,16,32,64)
   int ep;      // padded expert count (multiple of ee)
-  int kce;     // elements per K chunk
   int nkc;     // K chunks
   int mpad;    // padded rows of the fp64 gate matrix
   int nb;      // 64-token tiles
@@ -44,9 +40,8 @@ RoutePlan route_plan(const moe_config_t& c) {
   int e = c.n_experts;
   p.ee = e <= 8 ? 8 : e <= 16 ? 16 : e <= 32 ? 32 : 64;
   p.ep = ceil_div(e, p.ee) * p.ee;
-  p.kce = kRowBytes / (int)elem_size(c.dtype);
-  p.nkc = ceil_div(c.d_model, p.kce);
-  p.mpad = p.nkc * p.kce;
+  p.nkc = ceil_div(c.d_model, kKC);
+  p.mpad = p.nkc * kKC;
   p.nb = ceil_div(c.n_tokens, kTile);
   size_t o = 0;
   p.off_wd = o; o += align_up((size_t)p.mpad * p.ep * sizeof(double), 256);
@@ -85,81 +80,130 @@ template <> struct Widen<float> {
   }
 };
 
-template <typename T, int EE>
+// logits = fp32(x.W_g + b_g) with the products and the sum in fp64, then top-k, G(I) and the
+// histogram of choices, for one tile of 64 tokens.  The fp64 GEMM is register tiled: a thread owns
+// 8 tokens x 8 experts for a slice of every 64-wide K chunk; x (widened to fp64 while it is staged)
+// and the fp64 copy of W_g come from LDS, double buffered, with the next chunk's global loads in
+// flight under the FMAs.  The K slices are then summed in slice order (fixed, so runs repeat).
+template <typename T, int NEG>  // NEG groups of 8 experts per pass
 __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
     const T* __restrict__ x, const double* __restrict__ wd, const float* __restrict__ b_gate,
     float* __restrict__ logits, float* __restrict__ probs, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     int32_t* __restrict__ hist, int n_tokens, int d_model, int n_experts, int top_k, int renormalize, int ep, int nkc,
     int nb) {
+  constexpr int EE = 8 * NEG;         // experts per pass
+  constexpr int NKS = 32 / NEG;       // K slices
+  constexpr int KPS = kKC / NKS;      // k per slice and chunk
+  constexpr int R = NKS / 4;          // slices summed per reduction round
+  constexpr int V = Widen<T>::kN;     // elements per 16-byte load
+  constexpr int XLD = kTile * kKC / V / kGateThreads;  // 16-byte x loads per thread and chunk
+  constexpr int WLD = kKC * EE / 2 / kGateThreads;     // 16-byte W loads per thread and chunk
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* xs = smem;                                       // [kTile][kRowStride]
-  double* red = reinterpret_cast<double*>(smem + kTile * kRowStride);  // [EE][kTile]
-  float* lg = reinterpret_cast<float*>(red + EE * kTile);         // [kTile][n_experts + 1]
+  double* xs = reinterpret_cast<double*>(smem);                        // [2][kKC][kXP]; later partial sums
+  double* ws = xs + 2 * kKC * kXP;                                     // [2][kKC][EE]
+  float* lg = reinterpret_cast<float*>(ws + 2 * kKC * EE);             // [kTile][n_experts + 1]
   int32_t* hcnt = reinterpret_cast<int32_t*>(lg + kTile * (n_experts + 1));  // [top_k][n_experts]
+  double* part = xs;                    // [R][EE][kTile] after the K loop
+  double* red = xs + R * EE * kTile;    // [EE][kTile]
 
-  constexpr int V = Widen<T>::kN;
-  constexpr int KCE = kRowBytes / (int)sizeof(T);
-  constexpr int kLoads = kTile * kRowBytes / 16 / kGateThreads;  // 16-byte loads per thread per chunk (4)
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = tid >> 6;
+  const int tg = tid & 7, eg = (tid >> 3) % NEG, ks = tid / (8 * NEG);
   const int t0 = blockIdx.x * kTile;
   const int lgs = n_experts + 1;
 
   for (int i = tid; i < top_k * n_experts; i += kGateThreads) hcnt[i] = 0;
 
   for (int ec = 0; ec < ep; ec += EE) {
-    double acc[EE];
+    double acc[8][8];
 #pragma unroll
-    for (int e = 0; e < EE; ++e) acc[e] = 0.0;
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = 0.0;
 
-    uint4 pre[kLoads];
+    uint4 xr[XLD];
+    double2 wr[WLD];
     auto fetch = [&](int kc) {
 #pragma unroll
-      for (int r = 0; r < kLoads; ++r) {
-        int idx = tid + kGateThreads * r;
-        int row = idx / (kRowBytes / 16), c16 = idx % (kRowBytes / 16);
-        int t = t0 + row, k = kc * KCE + c16 * V;
-        pre[r] = (t < n_tokens && k < d_model) ? *reinterpret_cast<const uint4*>(x + (size_t)t * d_model + k)
-                                               : make_uint4(0, 0, 0, 0);
+      for (int r = 0; r < XLD; ++r) {
+        const int q = tid + kGateThreads * r;
+        const int row = q / (kKC / V), c = q % (kKC / V);
+        const int t = t0 + row, k = kc * kKC + c * V;
+        xr[r] = (t < n_tokens && k < d_model) ? *reinterpret_cast<const uint4*>(x + (size_t)t * d_model + k)
+                                              : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < WLD; ++r) {
+        const int q = tid + kGateThreads * r;
+        const int row = q / (EE / 2), c2 = q % (EE / 2);
+        wr[r] = *reinterpret_cast<const double2*>(wd + (size_t)(kc * kKC + row) * ep + ec + 2 * c2);
       }
     };
-    fetch(0);
-    for (int kc = 0; kc < nkc; ++kc) {
-      __syncthreads();  // previous chunk fully consumed
+    auto stash = [&](int buf) {
+      double* xb = xs + buf * kKC * kXP;
+      double* wb = ws + buf * kKC * EE;
 #pragma unroll
-      for (int r = 0; r < kLoads; ++r) {
-        int idx = tid + kGateThreads * r;
-        int row = idx / (kRowBytes / 16), c16 = idx % (kRowBytes / 16);
-        *reinterpret_cast<uint4*>(xs + row * kRowStride + c16 * 16) = pre[r];
-      }
-      __syncthreads();
-      if (kc + 1 < nkc) fetch(kc + 1);
-      // this wave's share of the chunk: bytes [wave*64, wave*64+64) of every row
-      const unsigned char* my = xs + lane * kRowStride + wave * (kRowBytes / kWaves);
-      const int kw = kc * KCE + wave * (KCE / kWaves);
-#pragma unroll
-      for (int c = 0; c < kRowBytes / kWaves / 16; ++c) {
-        uint4 r = *reinterpret_cast<const uint4*>(my + c * 16);
+      for (int r = 0; r < XLD; ++r) {
+        const int q = tid + kGateThreads * r;
+        const int row = q / (kKC / V), c = q % (kKC / V);
         double xd[V];
-        Widen<T>::run(r, xd);
+        Widen<T>::run(xr[r], xd);
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-          const double* __restrict__ wr = wd + (size_t)(kw + c * V + i) * ep + ec;  // wave-uniform address
-#pragma unroll
-          for (int e = 0; e < EE; ++e) acc[e] = fma(xd[i], wr[e], acc[e]);
-        }
+        for (int i = 0; i < V; ++i) xb[(c * V + i) * kXP + row] = xd[i];
       }
-    }
-    // sum the eight K slices in wave order
-    for (int w = 0; w < kWaves; ++w) {
-      __syncthreads();
-      if (wave == w) {
 #pragma unroll
-        for (int e = 0; e < EE; ++e) red[e * kTile + lane] = (w == 0 ? 0.0 : red[e * kTile + lane]) + acc[e];
+      for (int r = 0; r < WLD; ++r) {
+        const int q = tid + kGateThreads * r;
+        const int row = q / (EE / 2), c2 = q % (EE / 2);
+        *reinterpret_cast<double2*>(wb + row * EE + 2 * c2) = wr[r];
       }
-    }
+    };
+
+    __syncthreads();  // the LDS of the previous pass (partial sums) is free again
+    fetch(0);
+    stash(0);
     __syncthreads();
+    for (int kc = 0; kc < nkc; ++kc) {
+      if (kc + 1 < nkc) fetch(kc + 1);
+      const double* xb = xs + (kc & 1) * kKC * kXP + 8 * tg;
+      const double* wb = ws + (kc & 1) * kKC * EE + 8 * eg;
+#pragma unroll 2
+      for (int kk = 0; kk < KPS; ++kk) {
+        const int k = ks * KPS + kk;
+        double xv[8], wv[8];
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) {
+          const double2 a = *reinterpret_cast<const double2*>(xb + k * kXP + i);
+          const double2 b = *reinterpret_cast<const double2*>(wb + k * EE + i);
+          xv[i] = a.x; xv[i + 1] = a.y; wv[i] = b.x; wv[i + 1] = b.y;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[i][j] = fma(xv[i], wv[j], acc[i][j]);
+      }
+      if (kc + 1 < nkc) stash((kc + 1) & 1);  // that buffer was last read in iteration kc-1
+      __syncthreads();
+    }
+    // sum the K slices in slice order: four rounds of R slices each
+    for (int rd = 0; rd < 4; ++rd) {
+      if (ks / R == rd) {
+        double* pp = part + (size_t)(ks % R) * EE * kTile;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) pp[(8 * eg + j) * kTile + 8 * tg + i] = acc[i][j];
+      }
+      __syncthreads();
+      for (int o = tid; o < EE * kTile; o += kGateThreads) {
+        double v = rd == 0 ? 0.0 : red[o];
+#pragma unroll
+        for (int sl = 0; sl < R; ++sl) v += part[(size_t)sl * EE * kTile + o];
+        red[o] = v;
+      }
+      __syncthreads();
+    }
     for (int i = tid; i < EE * kTile; i += kGateThreads) {
       int e = i / kTile, tk = i % kTile;
       if (ec + e < n_experts) {
@@ -308,18 +352,19 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t* __restric
   for (int r = a + blockIdx.x * blockDim.x + threadIdx.x; r < total; r += gridDim.x * blockDim.x) src_of_row[r] = -1;
 }
 
-template <typename T, int EE>
+template <typename T, int NEG>
 void launch_gate(const moe_config_t& c, const RoutePlan& p, const void* x, const double* wd, const float* b_gate,
                  float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* hist, hipStream_t s) {
-  size_t lds = (size_t)kTile * kRowStride + (size_t)EE * kTile * sizeof(double) +
+  constexpr int EE = 8 * NEG;
+  size_t lds = (size_t)2 * kKC * kXP * sizeof(double) + (size_t)2 * kKC * EE * sizeof(double) +
                (size_t)kTile * (c.n_experts + 1) * sizeof(float) + (size_t)c.top_k * c.n_experts * sizeof(int32_t);
   static bool attr_set = false;  // LDS above 64 KB must be requested once per kernel
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gate_topk_kernel<T, EE>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gate_topk_kernel<T, NEG>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gate_topk_kernel<T, EE>), dim3(p.nb), dim3(kGateThreads), lds, s, (const T*)x, wd, b_gate, logits,
+  hipLaunchKernelGGL((gate_topk_kernel<T, NEG>), dim3(p.nb), dim3(kGateThreads), lds, s, (const T*)x, wd, b_gate, logits,
                      probs, topk_idx, topk_w, hist, c.n_tokens, c.d_model, c.n_experts, c.top_k, c.renormalize, p.ep,
                      p.nkc, p.nb);
 }
@@ -338,10 +383,10 @@ moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, c
                      c.n_experts, p.mpad, p.ep);
   MOE_CHECK_LAUNCH();
   switch (p.ee) {
-    case 8: launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
-    case 16: launch_gate<T, 16>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
-    case 32: launch_gate<T, 32>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
-    default: launch_gate<T, 64>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
+    case 8: launch_gate<T, 1>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
+    case 16: launch_gate<T, 2>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
+    case 32: launch_gate<T, 4>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
+    default: launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
   }
   MOE_CHECK_LAUNCH();
   hipLaunchKernelGGL(scan_hist_kernel, dim3(c.n_experts), dim3(256), 0, s, hist, total, c.top_k * p.nb);
