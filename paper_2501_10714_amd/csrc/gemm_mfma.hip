@@ -277,38 +277,42 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
   const long a_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.A[1]) - reinterpret_cast<const unsigned char*>(p.A[0]) - nk1 * a_step : 0;
   const long b_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.B[1]) - reinterpret_cast<const unsigned char*>(p.B[0]) - nk1 * b_step : 0;
 
-  // Loads of K stage `it_load` into LDS stage S, one (A, B) pair of wave-level loads per call; after
-  // the last pair the pointers step to the next K stage.  Stages past the end re-fetch the last one
-  // (never read), so the number of loads in flight is the same in every iteration.
+  // Loads of K stage `it_load` into LDS stage S, one wave-level load per call (q = 0..7: A0 B0 A1 B1 ...);
+  // after the last one the pointers step to the next K stage.  Stages past the end re-fetch the last
+  // one (never read), so the number of loads in flight is the same in every iteration.
   int it_load = 0;
-  auto issue_pair = [&](auto stage_tag, int j) {
+  auto issue_one = [&](auto stage_tag, int q) {
     constexpr int S = decltype(stage_tag)::value;
-    if (j == 0) dma_set_base(lds_addr_of(stage_a<S>()) + wave * kRegionBytes + kPartBytes);
+    const int j = q >> 1;
+    const bool is_b = q & 1;
+    if (q == 0) dma_set_base(lds_addr_of(stage_a<S>()) + wave * kRegionBytes + kPartBytes);
     if (RAGGED_K) {
       // rows past the expert's last re-read its last row (finite data); the A rows are zeroed in
       // LDS once they have landed (see iteration()), so those products vanish
       const int k0 = it_load * BK;
-      const int over_a = max(0, k0 + ka[j] - (Kg - 1));
-      const int over_b = max(0, k0 + kb[j] - (Kg - 1));
-      dma_block<false>(ga[j] - (long)over_a * lda * 2, j);
-      dma_block<true>(gb[j] - (long)over_b * ldb * 2, j);
+      if (is_b) {
+        const int over_b = max(0, k0 + kb[j] - (Kg - 1));
+        dma_block<true>(gb[j] - (long)over_b * ldb * 2, j);
+      } else {
+        const int over_a = max(0, k0 + ka[j] - (Kg - 1));
+        dma_block<false>(ga[j] - (long)over_a * lda * 2, j);
+      }
     } else {
-      dma_block<false>(ga[j], j);
-      dma_block<true>(gb[j], j);
+      if (is_b) dma_block<true>(gb[j], j); else dma_block<false>(ga[j], j);
     }
-    if (j == kLoads - 1) {
+    if (q == 2 * kLoads - 1) {
       const bool last = it_load + 1 >= nk;
       const bool jump = it_load + 1 == nk1 && sum_pairs == 2;
       const long da_ = last ? 0 : a_step + (jump ? a_jump : 0);
       const long db_ = last ? 0 : b_step + (jump ? b_jump : 0);
 #pragma unroll
-      for (int q = 0; q < kLoads; ++q) { ga[q] += da_; gb[q] += db_; }
+      for (int u = 0; u < kLoads; ++u) { ga[u] += da_; gb[u] += db_; }
       it_load += last ? 0 : 1;
     }
   };
   auto issue = [&](auto stage_tag) {
 #pragma unroll
-    for (int j = 0; j < kLoads; ++j) issue_pair(stage_tag, j);
+    for (int q = 0; q < 2 * kLoads; ++q) issue_one(stage_tag, q);
   };
 
   f32x16 acc[4][4];
@@ -362,12 +366,14 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
       }
       ++it_cur;
     }
-    // first half: the loads of stage S+3, the first fragments (X) of this stage and the MFMAs of the
-    // previous stage's second half (Y), interleaved by hand: the loads are assembly statements and the
-    // scheduler keeps everything else on its side of them
+    // Eight regions of 4 MFMAs, each with one load of stage S+3 and two fragment reads, interleaved
+    // by hand (the loads are assembly statements and the scheduler keeps everything else on its side
+    // of them).  The texture path takes ~16 cycles per load and four waves share it, so the loads are
+    // spread over the whole stage instead of being bunched behind the barrier.
+    // First half: this stage's first fragments (X) under the MFMAs of the previous stage's second half (Y).
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      issue_pair(std::integral_constant<int, (S + 3) % kStages>{}, j);
+      issue_one(std::integral_constant<int, (S + 3) % kStages>{}, j);
       // B fragments first: the first MFMA on X needs all four of them, but only ax[0]
       if (j < 2) {
         bx[2 * j] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j) * 32, 0, lane);
@@ -382,10 +388,21 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
           acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[fn], ay[j], acc[j][fn], 0, 0, 0);
       }
     }
-    // second half: this stage's second fragments (Y) under the MFMAs of X
-    load_frags(ay, by, stage_a<S>(), stage_b<S>(), 1);
-    mfma_step(ax, bx);
-    interleave();
+    // Second half: this stage's second fragments (Y) under the MFMAs of X.
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      issue_one(std::integral_constant<int, (S + 3) % kStages>{}, 4 + j);
+      if (j < 2) {
+        by[2 * j] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j) * 32, 1, lane);
+        by[2 * j + 1] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j + 1) * 32, 1, lane);
+      } else {
+        ay[2 * j - 4] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 4) * 32, 1, lane);
+        ay[2 * j - 3] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 3) * 32, 1, lane);
+      }
+#pragma unroll
+      for (int fn = 0; fn < 4; ++fn)
+        acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[fn], ax[j], acc[j][fn], 0, 0, 0);
+    }
   };
 
   if (nk > 0) {
