@@ -105,6 +105,9 @@ __device__ __forceinline__ void stage_barrier() {
 __device__ __forceinline__ int kc_chunk_off(int row, int c) {
   return (row >> 6) * kRegionBytes + (row & 63) * 64 + ((c ^ ((row >> 2) & 3)) << 4);
 }
+// TR operand: 32-byte segment s of k-row k sits at position s ^ tr_swz(k): the 4 rows x 2 segments that
+// two 16-lane groups of one transposed read touch then fall into 8 different bank groups
+__device__ __forceinline__ int tr_swz(int k) { return (k & 3) << 1; }
 // TR operand: k-row k of the stage lives in wave region k / 8
 __device__ __forceinline__ int tr_row_off(int k) { return (k >> 3) * kRegionBytes + (k & 7) * 512; }
 
@@ -119,9 +122,9 @@ __device__ __forceinline__ bf16x8 read_tr(const unsigned char* op, int col0, int
   const int grp = lane >> 4, i = lane & 15;
   const int seg = (col0 >> 4) + (grp & 1);          // 16-column segment of the tile
   const int k = 16 * s + 8 * (grp >> 1) + (i >> 2);  // k-row this lane addresses for the first read
-  const int a0 = tr_row_off(k) + ((seg ^ (k & 15)) << 5) + ((i & 3) << 3);
+  const int a0 = tr_row_off(k) + ((seg ^ tr_swz(k)) << 5) + ((i & 3) << 3);
   const int k1 = k + 4;
-  const int a1 = tr_row_off(k1) + ((seg ^ (k1 & 15)) << 5) + ((i & 3) << 3);
+  const int a1 = tr_row_off(k1) + ((seg ^ tr_swz(k1)) << 5) + ((i & 3) << 3);
   typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(op + a0));
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(op + a1));
@@ -241,7 +244,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         ka[j] = 0;
       } else {  // 2 k-rows x 512 B per block; ragged K: [k][i], i = weight-gradient row, clamped to the matrix
         const int krow = blk * 2 + (lane >> 5), pos = lane & 31;
-        const int seg = (pos >> 1) ^ (krow & 15);
+        const int seg = (pos >> 1) ^ tr_swz(krow);
         const int i0 = min(t.mt * BM + (seg * 2 + (pos & 1)) * 8, p.Mfix - 8);
         ga[j] = reinterpret_cast<const unsigned char*>(A + (long)(t.r0 + krow) * lda + i0);
         ka[j] = krow;
@@ -254,7 +257,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         kb[j] = 0;
       } else {
         const int krow = blk * 2 + (lane >> 5), pos = lane & 31;
-        const int seg = (pos >> 1) ^ (krow & 15);
+        const int seg = (pos >> 1) ^ tr_swz(krow);
         const int cc = seg * 2 + (pos & 1);  // 8-column chunk of the tile
         int col;
         const bf16_t* B = B0;
