@@ -1,14 +1,14 @@
 // Gate, top-k, capacity positions (FSMoE Sec. 2.1 "Gating Function" and the capacity rule of the
 // ordering function) and the gate's backward pass (Sec. 4.4).
 //
-// Forward, five launches on one stream:
+// Forward, four launches on one stream:
 //   1. widen_gate_kernel   W_g -> fp64, zero padded to [Mpad][EP]          (tiny)
 //   2. gate_topk_kernel    logits (fp64 accumulate, one rounding to fp32), top-k, G(I), and a
 //                          histogram of choices per (expert, rank j, 64-token tile)
 //   3. scan_hist_kernel    exclusive prefix over (j, tile) for every expert: the number of earlier
 //                          assignments to that expert in rank-major, token-minor order
-//   4. finalize_kernel     count = min(total, T), offsets = exclusive prefix of count
-//   5. positions_kernel    pos / row_of / src_of_row: tile base + rank among the wave's lanes
+//   4. positions_kernel    count = min(total, T), offsets = exclusive prefix of count, then
+//                          pos / row_of / src_of_row: tile base + rank among the wave's lanes
 // Positions come from prefix sums only (no atomics decide an index), so the result is the same on
 // every run and equals the serial walk "for j, for t".
 //
@@ -84,7 +84,9 @@ template <> struct Widen<float> {
 // histogram of choices, for one tile of 64 tokens.  The fp64 GEMM is register tiled: a thread owns
 // 8 tokens x 8 experts for a slice of every 64-wide K chunk; x (widened to fp64 while it is staged)
 // and the fp64 copy of W_g come from LDS, double buffered, with the next chunk's global loads in
-// flight under the FMAs.  The K slices are then summed in slice order (fixed, so runs repeat).
+// flight under the FMAs.  (The fp64 matrix instruction was tried for this product and measured slower.)
+// Eight consecutive lanes stage the same 16-byte column chunk of eight consecutive token rows, which
+// keeps the transposed LDS writes of the widened chunk nearly conflict-free.  The K slices are then summed in slice order (fixed, so runs repeat).
 template <typename T, int NEG>  // NEG groups of 8 experts per pass
 __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
     const T* __restrict__ x, const double* __restrict__ wd, const float* __restrict__ b_gate,
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
 #pragma unroll
       for (int r = 0; r < XLD; ++r) {
         const int q = tid + kGateThreads * r;
-        const int row = q / (kKC / V), c = q % (kKC / V);
+        const int row = (q & 7) + 8 * (q / (8 * (kKC / V))), c = (q >> 3) % (kKC / V);
         const int t = t0 + row, k = kc * kKC + c * V;
         xr[r] = (t < n_tokens && k < d_model) ? *reinterpret_cast<const uint4*>(x + (size_t)t * d_model + k)
                                               : make_uint4(0, 0, 0, 0);
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
 #pragma unroll
       for (int r = 0; r < XLD; ++r) {
         const int q = tid + kGateThreads * r;
-        const int row = q / (kKC / V), c = q % (kKC / V);
+        const int row = (q & 7) + 8 * (q / (8 * (kKC / V))), c = (q >> 3) % (kKC / V);  // as in fetch
         double xd[V];
         Widen<T>::run(xr[r], xd);
 #pragma unroll
@@ -297,27 +299,37 @@ __global__ __launch_bounds__(256) void scan_hist_kernel(int32_t* __restrict__ hi
   if (threadIdx.x == 255) total[blockIdx.x] = part[255];
 }
 
-__global__ void finalize_kernel(const int32_t* __restrict__ total, int32_t* __restrict__ count,
-                                int32_t* __restrict__ offsets, int n_experts, int capacity) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    int32_t run = 0;
-    for (int e = 0; e < n_experts; ++e) {
-      int32_t c = total[e];
-      if (capacity > 0 && c > capacity) c = capacity;
-      count[e] = c;
-      offsets[e] = run;
-      run += c;
-    }
-    offsets[n_experts] = run;
-  }
-}
-
-// One wave per 64-token tile, one token per lane.
+// One wave per 64-token tile, one token per lane.  Every block first derives count = min(total, T)
+// and offsets = exclusive prefix of count from the per-expert totals (E <= 256 values, redundantly per
+// block; block 0 also writes them out).
 __global__ __launch_bounds__(256) void positions_kernel(const int32_t* __restrict__ topk_idx,
                                                         const int32_t* __restrict__ base,
-                                                        const int32_t* __restrict__ offsets, int32_t* __restrict__ pos,
+                                                        const int32_t* __restrict__ total, int32_t* __restrict__ count,
+                                                        int32_t* __restrict__ offsets, int32_t* __restrict__ pos,
                                                         int32_t* __restrict__ row_of, int32_t* __restrict__ src_of_row,
                                                         int n_tokens, int n_experts, int top_k, int capacity, int nb) {
+  __shared__ int32_t s_off[257];
+  {
+    const int e = threadIdx.x;
+    int32_t c = 0;
+    if (e < n_experts) {
+      c = total[e];
+      if (capacity > 0 && c > capacity) c = capacity;
+    }
+    s_off[e + 1] = c;
+    if (e == 0) s_off[0] = 0;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {  // inclusive scan of s_off[1..256]
+      const int32_t v = e >= o ? s_off[e + 1 - o] : 0;
+      __syncthreads();
+      s_off[e + 1] += v;
+      __syncthreads();
+    }
+    if (blockIdx.x == 0) {
+      if (e < n_experts) { count[e] = c; offsets[e] = s_off[e]; }
+      if (e == 0) offsets[n_experts] = s_off[n_experts];
+    }
+  }
   const int lane = threadIdx.x & 63;
   const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int t = tile * kTile + lane;
@@ -339,7 +351,7 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t* __restric
         const int rank = base[((size_t)e * top_k + j) * nb + tile] + local;
         const bool kept = capacity <= 0 || rank < capacity;
         const int p = kept ? rank : -1;
-        const int row = kept ? offsets[e] + rank : -1;
+        const int row = kept ? s_off[e] + rank : -1;
         pos[(size_t)t * top_k + j] = p;
         row_of[(size_t)t * top_k + j] = row;
         if (kept) src_of_row[row] = t * top_k + j;
@@ -347,9 +359,9 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t* __restric
     }
   }
   // rows past A have no source
-  const int a = offsets[n_experts];
-  const int total = n_tokens * top_k;
-  for (int r = a + blockIdx.x * blockDim.x + threadIdx.x; r < total; r += gridDim.x * blockDim.x) src_of_row[r] = -1;
+  const int a = s_off[n_experts];
+  const int all = n_tokens * top_k;
+  for (int r = a + blockIdx.x * blockDim.x + threadIdx.x; r < all; r += gridDim.x * blockDim.x) src_of_row[r] = -1;
 }
 
 template <typename T, int NEG>
@@ -391,10 +403,8 @@ moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, c
   MOE_CHECK_LAUNCH();
   hipLaunchKernelGGL(scan_hist_kernel, dim3(c.n_experts), dim3(256), 0, s, hist, total, c.top_k * p.nb);
   MOE_CHECK_LAUNCH();
-  hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(64), 0, s, total, count, offsets, c.n_experts, c.capacity);
-  MOE_CHECK_LAUNCH();
-  hipLaunchKernelGGL(positions_kernel, dim3(ceil_div(p.nb, 4)), dim3(256), 0, s, topk_idx, hist, offsets, pos, row_of,
-                     src_of_row, c.n_tokens, c.n_experts, c.top_k, c.capacity, p.nb);
+  hipLaunchKernelGGL(positions_kernel, dim3(ceil_div(p.nb, 4)), dim3(256), 0, s, topk_idx, hist, total, count, offsets,
+                     pos, row_of, src_of_row, c.n_tokens, c.n_experts, c.top_k, c.capacity, p.nb);
   MOE_CHECK_LAUNCH();
   return MOE_OK;
 }
