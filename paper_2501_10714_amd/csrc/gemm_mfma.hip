@@ -505,8 +505,9 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         load8(static_cast<const bf16_t*>(p.X[1]) + off, a3);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          d1[j] = v[j] * a3[j] * silu_gradf_(a1[j]);
-          d3[j] = v[j] * siluf_(a1[j]);
+          const float sg = sigmoidf_(a1[j]);
+          d1[j] = v[j] * a3[j] * (sg * (1.0f + a1[j] * (1.0f - sg)));  // dhh * a3 * silu'(a1)
+          d3[j] = v[j] * (a1[j] * sg);                                   // dhh * silu(a1)
         }
         store8(static_cast<bf16_t*>(p.C[0]) + off, d1);
         store8(static_cast<bf16_t*>(p.C[1]) + off, d3);
