@@ -434,18 +434,48 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
   // the (now idle) LDS, 32 rows at a time in fp32, and reads it back row-major: a lane then owns 8
   // consecutive columns, 16 lanes cover 256 contiguous bytes of a row, and all global loads and
   // stores of the fused epilogues are 16-byte vectors on full cache lines.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end have landed
-  __syncthreads();                                  // every wave is done with the K stages
   float* scr = reinterpret_cast<float*>(wave == 0 ? g_st0 : wave == 1 ? g_st1 : wave == 2 ? g_st2 : g_st3);
   constexpr int kPitch = 128 + 4;  // floats per scratch row (+16 bytes: conflict-free 16-byte column writes)
   const int m_limit = RAGGED_K ? p.Mfix : t.rows;
   constexpr int kLanesPerRow = kGluFwd ? 8 : 16;   // 8 columns per lane
   constexpr int kRowsPerPass = 64 / kLanesPerRow;
+  constexpr int kPasses = 32 / kRowsPerPass;
   const int pr = lane / kLanesPerRow, c8 = (lane % kLanesPerRow) * 8;
   const int col = kGluFwd ? t.nt * kOutCols + wn * 64 + c8 : t.nt * BN + wn * 128 + c8;
   const bool col_ok = col < p.N;  // N is a multiple of 8
+  auto out_off = [&](int mrow, int c) {
+    return (RAGGED_K ? (long)t.e * p.gC + (long)mrow * p.ldc : (long)(t.r0 + mrow) * p.ldc) + c;
+  };
+  // The backward epilogues read the saved pre-activations at the output position.  The loads of a
+  // 32-row block go out one block ahead (addresses clamped into the tensor, so they need no
+  // predicate), and their latency passes under the LDS turn of the block before.
+  constexpr int kNX = EPI == EPI_GLU_BWD ? 2 : EPI == EPI_ACT_BWD ? 1 : 0;
+  u32x4 xin[2][kPasses][kNX > 0 ? kNX : 1];
+  auto prefetch = [&](int fm) {
+    if constexpr (kNX > 0) {
+      const int cc = min(col, p.N - 8);
+#pragma unroll
+      for (int ps = 0; ps < kPasses; ++ps) {
+        const int mrow = min(t.mt * BM + wm * 128 + fm * 32 + ps * kRowsPerPass + pr, m_limit - 1);
+        const long off = out_off(mrow, cc);
+#pragma unroll
+        for (int x = 0; x < kNX; ++x) xin[fm & 1][ps][x] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.X[x]) + off);
+      }
+    }
+  };
+  auto widen8 = [](const u32x4& r, float* v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(r[i] << 16);
+      v[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
+    }
+  };
+  prefetch(0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end have landed
+  __syncthreads();                                  // every wave is done with the K stages
 #pragma unroll
   for (int fm = 0; fm < 4; ++fm) {
+    if (fm + 1 < 4) prefetch(fm + 1);
 #pragma unroll
     for (int fn = 0; fn < 4; ++fn)
 #pragma unroll
@@ -454,7 +484,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         *reinterpret_cast<f32x4*>(scr + (lane & 31) * kPitch + fn * 32 + rg * 8 + (lane >> 5) * 4) = v;
       }
 #pragma unroll
-    for (int ps = 0; ps < 32 / kRowsPerPass; ++ps) {
+    for (int ps = 0; ps < kPasses; ++ps) {
       const int r = ps * kRowsPerPass + pr;
       const int mrow = t.mt * BM + wm * 128 + fm * 32 + r;  // row inside the group
       float v[8];
@@ -472,7 +502,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         for (int j = 0; j < 4; ++j) { g[j] = lo[j]; g[4 + j] = hi[j]; }
       }
       if (mrow >= m_limit || !col_ok) continue;
-      const long off = (RAGGED_K ? (long)t.e * p.gC + (long)mrow * p.ldc : (long)(t.r0 + mrow) * p.ldc) + col;
+      const long off = out_off(mrow, col);
       if (EPI == EPI_PLAIN) {
         bf16_t* c = static_cast<bf16_t*>(p.C[RAGGED_K ? t.set : 0]) + off;
         if (p.accumulate) {
@@ -495,14 +525,14 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         store8(static_cast<bf16_t*>(p.C[2]) + off, v);
       } else if (EPI == EPI_ACT_BWD) {
         float a1[8];
-        load8(static_cast<const bf16_t*>(p.X[0]) + off, a1);
+        widen8(xin[fm & 1][ps][0], a1);
 #pragma unroll
         for (int j = 0; j < 8; ++j) v[j] *= act_grad(a1[j], ACT);
         store8(static_cast<bf16_t*>(p.C[0]) + off, v);
       } else {
         float a1[8], a3[8], d1[8], d3[8];
-        load8(static_cast<const bf16_t*>(p.X[0]) + off, a1);
-        load8(static_cast<const bf16_t*>(p.X[1]) + off, a3);
+        widen8(xin[fm & 1][ps][0], a1);
+        widen8(xin[fm & 1][ps][kNX > 1 ? 1 : 0], a3);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const float sg = sigmoidf_(a1[j]);
