@@ -34,6 +34,7 @@
 // range tiles are ordered in bands of 8 row-tiles x all column-tiles so the 32 CUs of an XCD share
 // A and B panels in L2.  Rows are ragged per expert: the tile list is derived from offsets[] on
 // the device by every workgroup (E <= 256 scalar steps), no host synchronisation.
+#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -202,6 +203,131 @@ __device__ __forceinline__ TileId find_tile(const GemmP& p, int n_nt, int mt_fix
   t.rows = p.offsets[t.e + 1] - t.r0;
   t.valid = true;
   return t;
+}
+
+// ---- epilogue.  In the accumulators a lane holds 4 consecutive columns of 32 different rows
+// (acc[fm][fn][4 rg + j] = C[wm*128 + fm*32 + lane%32][wn*128 + fn*32 + rg*8 + (lane/32)*4 + j]);
+// stored like that, every store instruction would scatter 16-byte pieces over 32 rows and the L2
+// write path would set the pace.  Each wave therefore passes its quadrant through its own 32 KB of
+// the (now idle) LDS, 32 rows at a time in fp32, and reads it back row-major: a lane then owns 8
+// consecutive columns, 16 lanes cover 256 contiguous bytes of a row, and all global loads and
+// stores of the fused epilogues are 16-byte vectors on full cache lines.
+// Must be entered by all four waves; waits for every outstanding direct-to-LDS load first.
+template <int EPI, bool RAGGED_K, int ACT>
+__device__ __forceinline__ void tile_epilogue(const GemmP& p, const TileId& t, f32x16 (&acc)[4][4], int wave, int lane) {
+  constexpr bool kGluFwd = EPI == EPI_GLU_FWD;
+  constexpr int kOutCols = kGluFwd ? BN / 2 : BN;
+  const int wm = wave >> 1, wn = wave & 1;
+  float* scr = reinterpret_cast<float*>(wave == 0 ? g_st0 : wave == 1 ? g_st1 : wave == 2 ? g_st2 : g_st3);
+  constexpr int kPitch = 128 + 4;  // floats per scratch row (+16 bytes: conflict-free 16-byte column writes)
+  const int m_limit = RAGGED_K ? p.Mfix : t.rows;
+  constexpr int kLanesPerRow = kGluFwd ? 8 : 16;   // 8 columns per lane
+  constexpr int kRowsPerPass = 64 / kLanesPerRow;
+  constexpr int kPasses = 32 / kRowsPerPass;
+  const int pr = lane / kLanesPerRow, c8 = (lane % kLanesPerRow) * 8;
+  const int col = kGluFwd ? t.nt * kOutCols + wn * 64 + c8 : t.nt * BN + wn * 128 + c8;
+  const bool col_ok = col < p.N;  // N is a multiple of 8
+  auto out_off = [&](int mrow, int c) {
+    return (RAGGED_K ? (long)t.e * p.gC + (long)mrow * p.ldc : (long)(t.r0 + mrow) * p.ldc) + c;
+  };
+  // The backward epilogues read the saved pre-activations at the output position.  The loads of a
+  // 32-row block go out one block ahead (addresses clamped into the tensor, so they need no
+  // predicate), and their latency passes under the LDS turn of the block before.
+  constexpr int kNX = EPI == EPI_GLU_BWD ? 2 : EPI == EPI_ACT_BWD ? 1 : 0;
+  u32x4 xin[2][kPasses][kNX > 0 ? kNX : 1];
+  auto prefetch = [&](int fm) {
+    if constexpr (kNX > 0) {
+      const int cc = min(col, p.N - 8);
+#pragma unroll
+      for (int ps = 0; ps < kPasses; ++ps) {
+        const int mrow = min(t.mt * BM + wm * 128 + fm * 32 + ps * kRowsPerPass + pr, m_limit - 1);
+        const long off = out_off(mrow, cc);
+#pragma unroll
+        for (int x = 0; x < kNX; ++x) xin[fm & 1][ps][x] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.X[x]) + off);
+      }
+    }
+  };
+  auto widen8 = [](const u32x4& r, float* v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(r[i] << 16);
+      v[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
+    }
+  };
+  prefetch(0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end have landed
+  __syncthreads();                                  // every wave is done with the K stages
+#pragma unroll
+  for (int fm = 0; fm < 4; ++fm) {
+    if (fm + 1 < 4) prefetch(fm + 1);
+#pragma unroll
+    for (int fn = 0; fn < 4; ++fn)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        f32x4 v = {acc[fm][fn][4 * rg], acc[fm][fn][4 * rg + 1], acc[fm][fn][4 * rg + 2], acc[fm][fn][4 * rg + 3]};
+        *reinterpret_cast<f32x4*>(scr + (lane & 31) * kPitch + fn * 32 + rg * 8 + (lane >> 5) * 4) = v;
+      }
+#pragma unroll
+    for (int ps = 0; ps < kPasses; ++ps) {
+      const int r = ps * kRowsPerPass + pr;
+      const int mrow = t.mt * BM + wm * 128 + fm * 32 + r;  // row inside the group
+      float v[8];
+      {
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr + r * kPitch + c8);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr + r * kPitch + c8 + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { v[j] = lo[j]; v[4 + j] = hi[j]; }
+      }
+      float g[8];
+      if (kGluFwd) {
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr + r * kPitch + 64 + c8);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr + r * kPitch + 64 + c8 + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { g[j] = lo[j]; g[4 + j] = hi[j]; }
+      }
+      if (mrow >= m_limit || !col_ok) continue;
+      const long off = out_off(mrow, col);
+      if (EPI == EPI_PLAIN) {
+        bf16_t* c = static_cast<bf16_t*>(p.C[RAGGED_K ? t.set : 0]) + off;
+        if (p.accumulate) {
+          float old[8];
+          load8(c, old);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) v[j] += old[j];
+        }
+        store8(c, v);
+      } else if (EPI == EPI_ACT_FWD) {
+        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = act_fwd(v[j], ACT);
+        store8(static_cast<bf16_t*>(p.C[2]) + off, v);
+      } else if (EPI == EPI_GLU_FWD) {
+        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
+        store8(static_cast<bf16_t*>(p.C[1]) + off, g);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = siluf_(v[j]) * g[j];
+        store8(static_cast<bf16_t*>(p.C[2]) + off, v);
+      } else if (EPI == EPI_ACT_BWD) {
+        float a1[8];
+        widen8(xin[fm & 1][ps][0], a1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] *= act_grad(a1[j], ACT);
+        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
+      } else {
+        float a1[8], a3[8], d1[8], d3[8];
+        widen8(xin[fm & 1][ps][0], a1);
+        widen8(xin[fm & 1][ps][kNX > 1 ? 1 : 0], a3);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float sg = sigmoidf_(a1[j]);
+          d1[j] = v[j] * a3[j] * (sg * (1.0f + a1[j] * (1.0f - sg)));  // dhh * a3 * silu'(a1)
+          d3[j] = v[j] * (a1[j] * sg);                                   // dhh * silu(a1)
+        }
+        store8(static_cast<bf16_t*>(p.C[0]) + off, d1);
+        store8(static_cast<bf16_t*>(p.C[1]) + off, d3);
+      }
+    }
+  }
 }
 
 template <int LA, int LB, int EPI, bool RAGGED_K, int ACT>
@@ -427,123 +553,263 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end must land before the LDS goes back to the pool
   }
 
-  // ---- epilogue.  In the accumulators a lane holds 4 consecutive columns of 32 different rows
-  // (acc[fm][fn][4 rg + j] = C[wm*128 + fm*32 + lane%32][wn*128 + fn*32 + rg*8 + (lane/32)*4 + j]);
-  // stored like that, every store instruction would scatter 16-byte pieces over 32 rows and the L2
-  // write path would set the pace.  Each wave therefore passes its quadrant through its own 32 KB of
-  // the (now idle) LDS, 32 rows at a time in fp32, and reads it back row-major: a lane then owns 8
-  // consecutive columns, 16 lanes cover 256 contiguous bytes of a row, and all global loads and
-  // stores of the fused epilogues are 16-byte vectors on full cache lines.
-  float* scr = reinterpret_cast<float*>(wave == 0 ? g_st0 : wave == 1 ? g_st1 : wave == 2 ? g_st2 : g_st3);
-  constexpr int kPitch = 128 + 4;  // floats per scratch row (+16 bytes: conflict-free 16-byte column writes)
-  const int m_limit = RAGGED_K ? p.Mfix : t.rows;
-  constexpr int kLanesPerRow = kGluFwd ? 8 : 16;   // 8 columns per lane
-  constexpr int kRowsPerPass = 64 / kLanesPerRow;
-  constexpr int kPasses = 32 / kRowsPerPass;
-  const int pr = lane / kLanesPerRow, c8 = (lane % kLanesPerRow) * 8;
-  const int col = kGluFwd ? t.nt * kOutCols + wn * 64 + c8 : t.nt * BN + wn * 128 + c8;
-  const bool col_ok = col < p.N;  // N is a multiple of 8
-  auto out_off = [&](int mrow, int c) {
-    return (RAGGED_K ? (long)t.e * p.gC + (long)mrow * p.ldc : (long)(t.r0 + mrow) * p.ldc) + c;
-  };
-  // The backward epilogues read the saved pre-activations at the output position.  The loads of a
-  // 32-row block go out one block ahead (addresses clamped into the tensor, so they need no
-  // predicate), and their latency passes under the LDS turn of the block before.
-  constexpr int kNX = EPI == EPI_GLU_BWD ? 2 : EPI == EPI_ACT_BWD ? 1 : 0;
-  u32x4 xin[2][kPasses][kNX > 0 ? kNX : 1];
-  auto prefetch = [&](int fm) {
-    if constexpr (kNX > 0) {
-      const int cc = min(col, p.N - 8);
+  tile_epilogue<EPI, RAGGED_K, ACT>(p, t, acc, wave, lane);
+}
+
+// ============================================================================================
+// Second K pipeline, for products whose A operand is K-contiguous (all but the weight gradients)
+// and whose K is a multiple of 64.
+//
+// The L1 fills whole 128-byte lines: a direct-to-LDS load that takes only 64 bytes of each line (a
+// 32-k slice of a K-contiguous row) runs at half the rate of one that takes full lines (measured:
+// 29 vs 58 bytes/clk/CU from L2), and with two such operands the load path, not the matrix cores,
+// sets the pace.  Here a K-contiguous operand therefore arrives 64 k at a time: a batch is
+// [256 rows][64 k] = 32 KB, a wave-level load covers 8 rows x 128 bytes.  (A row-major B batch is
+// [64 k][256 columns], 2 k-rows x 512 bytes per load, as before.)
+//
+// LDS holds five batch buffers (160 KB).  Batches are issued in the order A0 B0 A1 B1 ..., batch j
+// into buffer j mod 5.  A 64-k step m multiplies batches 2m and 2m+1 in two halves of 32 k; during
+// its first half batch 2m+3 is issued (into the buffer that held A of step m-1), during its second
+// half batch 2m+4 (the buffer of B of step m-1).  So a batch has between one and three half-steps
+// to land, and one barrier per 64 k is enough: it says that every wave has batches 2m and 2m+1 and
+// has finished reading step m-1.  The loop is unrolled over five steps (the buffer assignment
+// repeats every ten batches), so every LDS access names its buffer statically.
+constexpr int BK2 = 64;
+constexpr int kBatchBytes = BM * BK2 * 2;  // 32 KB
+static_assert(kBatchBytes == 2 * kOpBytes, "a batch buffer is one of the 32 KB stage arrays");
+__shared__ __attribute__((aligned(1024))) unsigned char g_st4[kBatchBytes];
+
+template <int B> __device__ __forceinline__ unsigned char* batch_buf() {
+  if constexpr (B == 0) return g_st0; else if constexpr (B == 1) return g_st1; else if constexpr (B == 2) return g_st2;
+  else if constexpr (B == 3) return g_st3; else return g_st4;
+}
+// load q (0..7) of a wave's 8 KB share of a batch; M0 points at the middle of that share
+__device__ __forceinline__ void dma_block8(const unsigned char* g, int q) {
+  switch (q) {
+    case 0: dma16<-4096>(g); break;
+    case 1: dma16<-3072>(g); break;
+    case 2: dma16<-2048>(g); break;
+    case 3: dma16<-1024>(g); break;
+    case 4: dma16<0>(g); break;
+    case 5: dma16<1024>(g); break;
+    case 6: dma16<2048>(g); break;
+    default: dma16<3072>(g); break;
+  }
+}
+__device__ __forceinline__ void batch_barrier() {
+  asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+// K-contiguous batch: 128-byte rows, 16-byte chunk c of row r at position c ^ ((r >> 1) & 7): the 16
+// rows a quarter-wave reads with one ds_read_b128 pass then cover all 64 banks once
+__device__ __forceinline__ int kc64_swz(int row) { return (row >> 1) & 7; }
+__device__ __forceinline__ bf16x8 read_kc64(const unsigned char* op, int row0, int ks, int lane) {
+  const int row = row0 + (lane & 31);
+  const int c = 2 * ks + (lane >> 5);
+  return *reinterpret_cast<const bf16x8*>(op + row * 128 + ((c ^ kc64_swz(row)) << 4));
+}
+// row-major batch: k-row k at k * 512, segments swizzled as in the 32-k stages
+__device__ __forceinline__ bf16x8 read_tr64(const unsigned char* op, int col0, int ks, int lane) {
+  const int grp = lane >> 4, i = lane & 15;
+  const int seg = (col0 >> 4) + (grp & 1);
+  const int k = 16 * ks + 8 * (grp >> 1) + (i >> 2);
+  const int a0 = k * 512 + ((seg ^ tr_swz(k)) << 5) + ((i & 3) << 3);
+  const int k1 = k + 4;
+  const int a1 = k1 * 512 + ((seg ^ tr_swz(k1)) << 5) + ((i & 3) << 3);
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(op + a0));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(op + a1));
+  union { s16x4 h[2]; bf16x8 v; } u;
+  u.h[0] = lo; u.h[1] = hi;
+  return u.v;
+}
+
+template <int LB, int EPI, int ACT>
+__global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_nt) {
+  constexpr bool kGluFwd = EPI == EPI_GLU_FWD;
+  constexpr int kOutCols = kGluFwd ? BN / 2 : BN;
+
+  const TileId t = find_tile<false>(p, n_nt, 0);
+  if (!t.valid) return;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const int sum_pairs = !kGluFwd ? p.n_pairs : 1;
+  const int nb1 = p.Kfix / BK2;     // 64-k steps per operand pair
+  const int nb = nb1 * sum_pairs;   // 64-k steps in all
+
+  const long lda = p.sAi;
+  const long ldb = LB == TR ? p.sBk : p.sBn;
+  const unsigned char* ga[8];
+  const unsigned char* gb[8];
+  {
+    const bf16_t* A = static_cast<const bf16_t*>(p.A[0]);
+    const bf16_t* B0 = static_cast<const bf16_t*>(p.B[0]);
+    const bf16_t* B1 = kGluFwd ? static_cast<const bf16_t*>(p.B[1]) : B0;
 #pragma unroll
-      for (int ps = 0; ps < kPasses; ++ps) {
-        const int mrow = min(t.mt * BM + wm * 128 + fm * 32 + ps * kRowsPerPass + pr, m_limit - 1);
-        const long off = out_off(mrow, cc);
-#pragma unroll
-        for (int x = 0; x < kNX; ++x) xin[fm & 1][ps][x] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.X[x]) + off);
-      }
-    }
-  };
-  auto widen8 = [](const u32x4& r, float* v) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      v[2 * i] = __uint_as_float(r[i] << 16);
-      v[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
-    }
-  };
-  prefetch(0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end have landed
-  __syncthreads();                                  // every wave is done with the K stages
-#pragma unroll
-  for (int fm = 0; fm < 4; ++fm) {
-    if (fm + 1 < 4) prefetch(fm + 1);
-#pragma unroll
-    for (int fn = 0; fn < 4; ++fn)
-#pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        f32x4 v = {acc[fm][fn][4 * rg], acc[fm][fn][4 * rg + 1], acc[fm][fn][4 * rg + 2], acc[fm][fn][4 * rg + 3]};
-        *reinterpret_cast<f32x4*>(scr + (lane & 31) * kPitch + fn * 32 + rg * 8 + (lane >> 5) * 4) = v;
-      }
-#pragma unroll
-    for (int ps = 0; ps < kPasses; ++ps) {
-      const int r = ps * kRowsPerPass + pr;
-      const int mrow = t.mt * BM + wm * 128 + fm * 32 + r;  // row inside the group
-      float v[8];
-      {
-        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr + r * kPitch + c8);
-        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr + r * kPitch + c8 + 4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { v[j] = lo[j]; v[4 + j] = hi[j]; }
-      }
-      float g[8];
-      if (kGluFwd) {
-        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr + r * kPitch + 64 + c8);
-        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr + r * kPitch + 64 + c8 + 4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { g[j] = lo[j]; g[4 + j] = hi[j]; }
-      }
-      if (mrow >= m_limit || !col_ok) continue;
-      const long off = out_off(mrow, col);
-      if (EPI == EPI_PLAIN) {
-        bf16_t* c = static_cast<bf16_t*>(p.C[RAGGED_K ? t.set : 0]) + off;
-        if (p.accumulate) {
-          float old[8];
-          load8(c, old);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) v[j] += old[j];
+    for (int j = 0; j < 8; ++j) {
+      // K-contiguous: load j of this wave = rows 64 wave + 8 j .. + 7, lane i -> (row i / 8, slot i % 8)
+      const int row = wave * 64 + j * 8 + (lane >> 3), slot = lane & 7;
+      const int c = slot ^ kc64_swz(row);
+      const int grow = t.r0 + min(t.mt * BM + row, t.rows - 1);
+      ga[j] = reinterpret_cast<const unsigned char*>(A + (long)grow * lda + c * 8);
+      if (LB == KC) {
+        const int n = min(t.nt * BN + row, p.N - 1);
+        gb[j] = reinterpret_cast<const unsigned char*>(B0 + (long)t.e * p.gB + (long)n * ldb + c * 8);
+      } else {  // row-major: load j = k-rows 16 wave + 2 j, + 1; lane i -> (k-row i / 32, 16-byte slot i % 32)
+        const int krow = wave * 16 + j * 2 + (lane >> 5), pos = lane & 31;
+        const int seg = (pos >> 1) ^ tr_swz(krow);
+        const int cc = seg * 2 + (pos & 1);  // 8-column chunk of the tile
+        int col;
+        const bf16_t* B = B0;
+        if (kGluFwd) {  // tile columns: [wn][W1 64 | W3 64]
+          col = t.nt * kOutCols + (cc >> 4) * 64 + (cc & 7) * 8;
+          if ((cc >> 3) & 1) B = B1;
+        } else {
+          col = t.nt * BN + cc * 8;
         }
-        store8(c, v);
-      } else if (EPI == EPI_ACT_FWD) {
-        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = act_fwd(v[j], ACT);
-        store8(static_cast<bf16_t*>(p.C[2]) + off, v);
-      } else if (EPI == EPI_GLU_FWD) {
-        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
-        store8(static_cast<bf16_t*>(p.C[1]) + off, g);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = siluf_(v[j]) * g[j];
-        store8(static_cast<bf16_t*>(p.C[2]) + off, v);
-      } else if (EPI == EPI_ACT_BWD) {
-        float a1[8];
-        widen8(xin[fm & 1][ps][0], a1);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] *= act_grad(a1[j], ACT);
-        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
-      } else {
-        float a1[8], a3[8], d1[8], d3[8];
-        widen8(xin[fm & 1][ps][0], a1);
-        widen8(xin[fm & 1][ps][kNX > 1 ? 1 : 0], a3);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float sg = sigmoidf_(a1[j]);
-          d1[j] = v[j] * a3[j] * (sg * (1.0f + a1[j] * (1.0f - sg)));  // dhh * a3 * silu'(a1)
-          d3[j] = v[j] * (a1[j] * sg);                                   // dhh * silu(a1)
-        }
-        store8(static_cast<bf16_t*>(p.C[0]) + off, d1);
-        store8(static_cast<bf16_t*>(p.C[1]) + off, d3);
+        col = min(col, p.N - 8);
+        gb[j] = reinterpret_cast<const unsigned char*>(B + (long)t.e * p.gB + (long)krow * ldb + col);
       }
     }
   }
+  const long a_step = (long)BK2 * 2;  // bytes per batch
+  const long b_step = (LB == KC ? (long)BK2 : (long)BK2 * ldb) * 2;
+  const long a_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.A[1]) - reinterpret_cast<const unsigned char*>(p.A[0]) - nb1 * a_step : 0;
+  const long b_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.B[1]) - reinterpret_cast<const unsigned char*>(p.B[0]) - nb1 * b_step : 0;
+
+  // One wave-level load of the next A (or B) batch into buffer BUF; after the eighth the pointers step
+  // to the following batch.  Batches past the end re-fetch the last one into a free buffer (never
+  // read), so the number of loads in flight at a barrier is always the same.
+  int ia = 0, ib = 0;
+  auto issue_a = [&](auto buf_tag, int q) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    if (q == 0) dma_set_base(lds_addr_of(batch_buf<BUF>()) + wave * 8192 + 4096);
+    dma_block8(ga[q], q);
+    if (q == 7) {
+      const bool last = ia + 1 >= nb;
+      const long d = last ? 0 : a_step + ((ia + 1 == nb1 && sum_pairs == 2) ? a_jump : 0);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) ga[u] += d;
+      ia += last ? 0 : 1;
+    }
+  };
+  auto issue_b = [&](auto buf_tag, int q) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    if (q == 0) dma_set_base(lds_addr_of(batch_buf<BUF>()) + wave * 8192 + 4096);
+    dma_block8(gb[q], q);
+    if (q == 7) {
+      const bool last = ib + 1 >= nb;
+      const long d = last ? 0 : b_step + ((ib + 1 == nb1 && sum_pairs == 2) ? b_jump : 0);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) gb[u] += d;
+      ib += last ? 0 : 1;
+    }
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  bf16x8 ax[4], bx[4], ay[4], by[4];  // fragment sets X (first 16 k of a half-step) and Y (second 16 k)
+  auto frag_a = [&](const unsigned char* buf, int f, int ks) { return read_kc64(buf, wm * 128 + f * 32, ks, lane); };
+  auto frag_b = [&](const unsigned char* buf, int f, int ks) {
+    return LB == KC ? read_kc64(buf, wn * 128 + f * 32, ks, lane) : read_tr64(buf, wn * 128 + f * 32, ks, lane);
+  };
+
+  // Half-step PH of the ten in a period: 64-k step U = PH / 2 of five, half H = PH % 2.
+  auto half_step = [&](auto ph_tag, auto first_tag) {
+    constexpr int PH = decltype(ph_tag)::value;
+    constexpr bool kFirst = decltype(first_tag)::value;
+    constexpr int U = PH / 2, H = PH % 2;
+    constexpr int ABUF = (2 * U) % 5, BBUF = (2 * U + 1) % 5;
+    constexpr int LBUF = H == 0 ? (2 * U + 3) % 5 : (2 * U + 4) % 5;  // H = 0 issues a B batch, H = 1 an A batch
+    const unsigned char* abuf = batch_buf<ABUF>();
+    const unsigned char* bbuf = batch_buf<BBUF>();
+    if (H == 0) batch_barrier();
+    // Eight regions of 4 MFMAs, each with one load and two fragment reads (see the 32-k kernel).
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (H == 0) issue_b(std::integral_constant<int, LBUF>{}, j); else issue_a(std::integral_constant<int, LBUF>{}, j);
+      if (j < 2) {
+        bx[2 * j] = frag_b(bbuf, 2 * j, 2 * H);
+        bx[2 * j + 1] = frag_b(bbuf, 2 * j + 1, 2 * H);
+      } else {
+        ax[2 * j - 4] = frag_a(abuf, 2 * j - 4, 2 * H);
+        ax[2 * j - 3] = frag_a(abuf, 2 * j - 3, 2 * H);
+      }
+      if (!kFirst) {
+#pragma unroll
+        for (int fn = 0; fn < 4; ++fn)
+          acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[fn], ay[j], acc[j][fn], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (H == 0) issue_b(std::integral_constant<int, LBUF>{}, 4 + j); else issue_a(std::integral_constant<int, LBUF>{}, 4 + j);
+      if (j < 2) {
+        by[2 * j] = frag_b(bbuf, 2 * j, 2 * H + 1);
+        by[2 * j + 1] = frag_b(bbuf, 2 * j + 1, 2 * H + 1);
+      } else {
+        ay[2 * j - 4] = frag_a(abuf, 2 * j - 4, 2 * H + 1);
+        ay[2 * j - 3] = frag_a(abuf, 2 * j - 3, 2 * H + 1);
+      }
+#pragma unroll
+      for (int fn = 0; fn < 4; ++fn)
+        acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[fn], ax[j], acc[j][fn], 0, 0, 0);
+    }
+  };
+#define MOE_HS(ph) half_step(std::integral_constant<int, ph>{}, std::false_type{})
+  if (nb > 0) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) issue_a(std::integral_constant<int, 0>{}, q);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) issue_b(std::integral_constant<int, 1>{}, q);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) issue_a(std::integral_constant<int, 2>{}, q);
+    half_step(std::integral_constant<int, 0>{}, std::true_type{});
+    const int nh = 2 * nb;  // half-steps
+    int h = 1;
+    for (; h + 10 <= nh; h += 10) {
+      MOE_HS(1); MOE_HS(2); MOE_HS(3); MOE_HS(4); MOE_HS(5); MOE_HS(6); MOE_HS(7); MOE_HS(8); MOE_HS(9); MOE_HS(0);
+    }
+    const int rest = nh - h;  // 0..9 half-steps left, starting at phase 1
+    if (rest > 0) MOE_HS(1);
+    if (rest > 1) MOE_HS(2);
+    if (rest > 2) MOE_HS(3);
+    if (rest > 3) MOE_HS(4);
+    if (rest > 4) MOE_HS(5);
+    if (rest > 5) MOE_HS(6);
+    if (rest > 6) MOE_HS(7);
+    if (rest > 7) MOE_HS(8);
+    if (rest > 8) MOE_HS(9);
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < 4; ++fn)
+        acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[fn], ay[fm], acc[fm][fn], 0, 0, 0);
+  }
+#undef MOE_HS
+  tile_epilogue<EPI, false, ACT>(p, t, acc, wave, lane);
+}
+
+template <int LB, int EPI, int ACT = 0>
+moe_status_t launch_cfg64(const GemmP& p, hipStream_t s) {
+  constexpr int out_cols = EPI == EPI_GLU_FWD ? BN / 2 : BN;
+  const int n_nt = ceil_div(p.N, out_cols);
+  long rows_bound = (long)p.max_rows * p.n_experts;
+  if (rows_bound > p.total_rows_bound) rows_bound = p.total_rows_bound;
+  const int max_tiles = (int)((rows_bound + BM - 1) / BM + p.n_experts) * n_nt;
+  if (max_tiles <= 0) return MOE_OK;
+  const int grid = ceil_div(max_tiles, 8) * 8;
+  hipLaunchKernelGGL((gg_mfma64_kernel<LB, EPI, ACT>), dim3(grid), dim3(kThreads), 0, s, p, n_nt);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
 }
 
 template <int LA, int LB, int EPI, bool RAGGED_K, int ACT = 0>
@@ -581,6 +847,23 @@ bool gemm_mfma_supported(const GemmP& p, int dtype, int epi, bool ragged_k) {
 moe_status_t launch_gemm_mfma(const GemmP& p, int epi, bool ragged_k, hipStream_t s) {
   if (ragged_k) return launch_cfg<TR, TR, EPI_PLAIN, true>(p, s);
   const bool b_kc = p.sBk == 1;  // B(k,n) = W[n][k]: the dgrad products
+  static const bool force_k32 = getenv("MOE_GEMM_K32") != nullptr;  // for A/B timing of the two K pipelines
+  if (p.Kfix % BK2 == 0 && !force_k32) {
+    switch (epi) {
+      case EPI_PLAIN:
+        return b_kc ? launch_cfg64<KC, EPI_PLAIN>(p, s) : launch_cfg64<TR, EPI_PLAIN>(p, s);
+      case EPI_ACT_FWD:
+        if (p.act == MOE_ACT_RELU) return launch_cfg64<TR, EPI_ACT_FWD, MOE_ACT_RELU>(p, s);
+        if (p.act == MOE_ACT_GELU_TANH) return launch_cfg64<TR, EPI_ACT_FWD, MOE_ACT_GELU_TANH>(p, s);
+        return launch_cfg64<TR, EPI_ACT_FWD, MOE_ACT_GELU_ERF>(p, s);
+      case EPI_GLU_FWD: return launch_cfg64<TR, EPI_GLU_FWD>(p, s);
+      case EPI_ACT_BWD:
+        if (p.act == MOE_ACT_RELU) return launch_cfg64<KC, EPI_ACT_BWD, MOE_ACT_RELU>(p, s);
+        if (p.act == MOE_ACT_GELU_TANH) return launch_cfg64<KC, EPI_ACT_BWD, MOE_ACT_GELU_TANH>(p, s);
+        return launch_cfg64<KC, EPI_ACT_BWD, MOE_ACT_GELU_ERF>(p, s);
+      default: return launch_cfg64<KC, EPI_GLU_BWD>(p, s);
+    }
+  }
   switch (epi) {
     case EPI_PLAIN:
       return b_kc ? launch_cfg<KC, KC, EPI_PLAIN, false>(p, s) : launch_cfg<KC, TR, EPI_PLAIN, false>(p, s);

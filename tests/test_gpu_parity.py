@@ -34,6 +34,8 @@ CASES = {
     "rows_block": S.scaled(W["mixtral"], N=200, M=2048, H=64, E=4, seed=27),
     "rows_loop": S.scaled(W["switch"], N=150, M=2304, H=64, E=4, seed=28),
     "rows_2waves_f32": S.scaled(W["tiny"], N=200, M=320, H=64, E=4, k=2, seed=29),
+    # M and H multiples of 32 but not of 64: the 32-k pipeline of the MFMA GEMM (the others take 64-k batches)
+    "k32_pipeline": S.scaled(W["mixtral"], N=600, M=160, H=224, E=4, seed=30),
 }
 
 
