@@ -596,6 +596,29 @@ __device__ __forceinline__ void dma_block8(const unsigned char* g, int q) {
     default: dma16<3072>(g); break;
   }
 }
+constexpr int kDmaBias = 4096;
+// a wave-uniform pointer the compiler may hold in vector registers (tile indices come out of
+// integer divisions, which run on the vector ALU) -> scalar registers
+__device__ __forceinline__ const unsigned char* to_sgpr(const unsigned char* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const unsigned char*>(((uint64_t)hi << 32) | lo);
+}
+template <int OFF> __device__ __forceinline__ void dma16s(uint32_t voff, const unsigned char* sbase) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(sbase), "n"(OFF) : "memory");
+}
+__device__ __forceinline__ void dma_block8s(uint32_t voff, const unsigned char* sbase, int q) {
+  switch (q) {
+    case 0: dma16s<-4096>(voff, sbase); break;
+    case 1: dma16s<-3072>(voff, sbase); break;
+    case 2: dma16s<-2048>(voff, sbase); break;
+    case 3: dma16s<-1024>(voff, sbase); break;
+    case 4: dma16s<0>(voff, sbase); break;
+    case 5: dma16s<1024>(voff, sbase); break;
+    case 6: dma16s<2048>(voff, sbase); break;
+    default: dma16s<3072>(voff, sbase); break;
+  }
+}
 __device__ __forceinline__ void batch_barrier() {
   asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
@@ -641,36 +664,49 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
 
   const long lda = p.sAi;
   const long ldb = LB == TR ? p.sBk : p.sBn;
-  const unsigned char* ga[8];
+  // Addresses of the direct-to-LDS loads: scalar base (steps along K) + 32-bit lane offset (fixed for the
+  // tile).  A wave is held at such a load while its addresses go out, and the MFMA queue drains
+  // meanwhile: about 18 cycles with a 64-bit address per lane, about 3 with a 32-bit offset (measured).
+  // The instruction adds its immediate offset to the LDS address and to the global address alike, so
+  // the lane offset carries kDmaBias - OFF and the scalar base is kDmaBias short.
+  // The Mixtral forward tile takes its columns from two tensors (W1 | W3): those loads keep a full
+  // address per lane.
+  constexpr bool kBPtr = kGluFwd;  // B loads with per-lane 64-bit addresses
+  uint32_t va[8], vb[8];
   const unsigned char* gb[8];
+  const unsigned char* sa;
+  const unsigned char* sb;
   {
     const bf16_t* A = static_cast<const bf16_t*>(p.A[0]);
     const bf16_t* B0 = static_cast<const bf16_t*>(p.B[0]);
     const bf16_t* B1 = kGluFwd ? static_cast<const bf16_t*>(p.B[1]) : B0;
+    sa = to_sgpr(reinterpret_cast<const unsigned char*>(A + (long)(t.r0 + t.mt * BM) * lda) - kDmaBias);
+    sb = to_sgpr(reinterpret_cast<const unsigned char*>(B0 + (long)t.e * p.gB + (LB == KC ? (long)t.nt * BN * ldb : (long)t.nt * BN)) - kDmaBias);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
+      const uint32_t bias = (uint32_t)(kDmaBias - (-4096 + 1024 * j));
       // K-contiguous: load j of this wave = rows 64 wave + 8 j .. + 7, lane i -> (row i / 8, slot i % 8)
       const int row = wave * 64 + j * 8 + (lane >> 3), slot = lane & 7;
       const int c = slot ^ kc64_swz(row);
-      const int grow = t.r0 + min(t.mt * BM + row, t.rows - 1);
-      ga[j] = reinterpret_cast<const unsigned char*>(A + (long)grow * lda + c * 8);
+      const int rrow = min(t.mt * BM + row, t.rows - 1) - t.mt * BM;  // rows past the expert's last re-read it
+      va[j] = (uint32_t)rrow * (uint32_t)(lda * 2) + c * 16 + bias;
+      vb[j] = 0;
+      gb[j] = nullptr;
       if (LB == KC) {
-        const int n = min(t.nt * BN + row, p.N - 1);
-        gb[j] = reinterpret_cast<const unsigned char*>(B0 + (long)t.e * p.gB + (long)n * ldb + c * 8);
+        const int rn = min(t.nt * BN + row, p.N - 1) - t.nt * BN;
+        vb[j] = (uint32_t)rn * (uint32_t)(ldb * 2) + c * 16 + bias;
       } else {  // row-major: load j = k-rows 16 wave + 2 j, + 1; lane i -> (k-row i / 32, 16-byte slot i % 32)
         const int krow = wave * 16 + j * 2 + (lane >> 5), pos = lane & 31;
         const int seg = (pos >> 1) ^ tr_swz(krow);
         const int cc = seg * 2 + (pos & 1);  // 8-column chunk of the tile
-        int col;
-        const bf16_t* B = B0;
         if (kGluFwd) {  // tile columns: [wn][W1 64 | W3 64]
-          col = t.nt * kOutCols + (cc >> 4) * 64 + (cc & 7) * 8;
-          if ((cc >> 3) & 1) B = B1;
+          const int col = min(t.nt * kOutCols + (cc >> 4) * 64 + (cc & 7) * 8, p.N - 8);
+          const bf16_t* B = ((cc >> 3) & 1) ? B1 : B0;
+          gb[j] = reinterpret_cast<const unsigned char*>(B + (long)t.e * p.gB + (long)krow * ldb + col);
         } else {
-          col = t.nt * BN + cc * 8;
+          const int rcol = min(t.nt * BN + cc * 8, p.N - 8) - t.nt * BN;
+          vb[j] = (uint32_t)krow * (uint32_t)(ldb * 2) + rcol * 2 + bias;
         }
-        col = min(col, p.N - 8);
-        gb[j] = reinterpret_cast<const unsigned char*>(B + (long)t.e * p.gB + (long)krow * ldb + col);
       }
     }
   }
@@ -679,31 +715,33 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
   const long a_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.A[1]) - reinterpret_cast<const unsigned char*>(p.A[0]) - nb1 * a_step : 0;
   const long b_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.B[1]) - reinterpret_cast<const unsigned char*>(p.B[0]) - nb1 * b_step : 0;
 
-  // One wave-level load of the next A (or B) batch into buffer BUF; after the eighth the pointers step
+  // One wave-level load of the next A (or B) batch into buffer BUF; after the eighth the base steps
   // to the following batch.  Batches past the end re-fetch the last one into a free buffer (never
   // read), so the number of loads in flight at a barrier is always the same.
   int ia = 0, ib = 0;
   auto issue_a = [&](auto buf_tag, int q) {
     constexpr int BUF = decltype(buf_tag)::value;
     if (q == 0) dma_set_base(lds_addr_of(batch_buf<BUF>()) + wave * 8192 + 4096);
-    dma_block8(ga[q], q);
+    dma_block8s(va[q], to_sgpr(sa), q);
     if (q == 7) {
       const bool last = ia + 1 >= nb;
-      const long d = last ? 0 : a_step + ((ia + 1 == nb1 && sum_pairs == 2) ? a_jump : 0);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) ga[u] += d;
+      sa += last ? 0 : a_step + ((ia + 1 == nb1 && sum_pairs == 2) ? a_jump : 0);
       ia += last ? 0 : 1;
     }
   };
   auto issue_b = [&](auto buf_tag, int q) {
     constexpr int BUF = decltype(buf_tag)::value;
     if (q == 0) dma_set_base(lds_addr_of(batch_buf<BUF>()) + wave * 8192 + 4096);
-    dma_block8(gb[q], q);
+    if (kBPtr) dma_block8(gb[q], q); else dma_block8s(vb[q], to_sgpr(sb), q);
     if (q == 7) {
       const bool last = ib + 1 >= nb;
       const long d = last ? 0 : b_step + ((ib + 1 == nb1 && sum_pairs == 2) ? b_jump : 0);
+      if (kBPtr) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) gb[u] += d;
+        for (int u = 0; u < 8; ++u) gb[u] += d;
+      } else {
+        sb += d;
+      }
       ib += last ? 0 : 1;
     }
   };
@@ -732,10 +770,13 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
     const unsigned char* abuf = batch_buf<ABUF>();
     const unsigned char* bbuf = batch_buf<BBUF>();
     if (H == 0) batch_barrier();
-    // Eight regions of 4 MFMAs, each with one load and two fragment reads (see the 32-k kernel).
+    // Eight regions of 4 MFMAs, each with one load and two fragment reads.
+    auto issue = [&](int q) {
+      if (H == 0) issue_b(std::integral_constant<int, LBUF>{}, q); else issue_a(std::integral_constant<int, LBUF>{}, q);
+    };
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      if (H == 0) issue_b(std::integral_constant<int, LBUF>{}, j); else issue_a(std::integral_constant<int, LBUF>{}, j);
+      issue(j);
       if (j < 2) {
         bx[2 * j] = frag_b(bbuf, 2 * j, 2 * H);
         bx[2 * j + 1] = frag_b(bbuf, 2 * j + 1, 2 * H);
@@ -748,10 +789,14 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
         for (int fn = 0; fn < 4; ++fn)
           acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[fn], ay[j], acc[j][fn], 0, 0, 0);
       }
+      // keep the region as written (the reads of the next fragments go out a half-step's worth of
+      // MFMAs before their use); left alone, the scheduler sinks them down to the use and the
+      // matrix pipe waits out the LDS latency twice per half-step
+      __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      if (H == 0) issue_b(std::integral_constant<int, LBUF>{}, 4 + j); else issue_a(std::integral_constant<int, LBUF>{}, 4 + j);
+      issue(4 + j);
       if (j < 2) {
         by[2 * j] = frag_b(bbuf, 2 * j, 2 * H + 1);
         by[2 * j + 1] = frag_b(bbuf, 2 * j + 1, 2 * H + 1);
@@ -762,6 +807,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
 #pragma unroll
       for (int fn = 0; fn < 4; ++fn)
         acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[fn], ax[j], acc[j][fn], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 #define MOE_HS(ph) half_step(std::integral_constant<int, ph>{}, std::false_type{})
