@@ -84,6 +84,26 @@ __device__ __forceinline__ void dma_set_base(uint32_t lds_addr) {
 template <int OFF> __device__ __forceinline__ void dma16(const unsigned char* g) {
   asm volatile("global_load_lds_dwordx4 %0, off offset:%1" ::"v"(g - OFF), "n"(OFF) : "memory");
 }
+constexpr int kDmaBias = 4096;
+// a wave-uniform pointer the compiler may hold in vector registers (tile indices come out of
+// integer divisions, which run on the vector ALU) -> scalar registers
+__device__ __forceinline__ const unsigned char* to_sgpr(const unsigned char* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const unsigned char*>(((uint64_t)hi << 32) | lo);
+}
+template <int OFF> __device__ __forceinline__ void dma16s(uint32_t voff, const unsigned char* sbase) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(sbase), "n"(OFF) : "memory");
+}
+template <bool IS_B> __device__ __forceinline__ void dma_block_s(uint32_t voff, const unsigned char* sbase, int j) {
+  constexpr int base = IS_B ? 0 : -kPartBytes;
+  switch (j) {
+    case 0: dma16s<base>(voff, sbase); break;
+    case 1: dma16s<base + 1024>(voff, sbase); break;
+    case 2: dma16s<base + 2048>(voff, sbase); break;
+    default: dma16s<base + 3072>(voff, sbase); break;
+  }
+}
 // block j of the A part (j = 0..3) or of the B part
 template <bool IS_B> __device__ __forceinline__ void dma_block(const unsigned char* g, int j) {
   constexpr int base = IS_B ? 0 : -kPartBytes;
@@ -352,62 +372,72 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
   //      chunk the swizzle puts there.  Pointers advance by a uniform stride per K stage.
   const long lda = RAGGED_K ? p.sAk : p.sAi;  // row stride (elements) of the A array in memory
   const long ldb = RAGGED_K ? p.sBk : (LB == TR ? p.sBk : p.sBn);
-  const unsigned char* ga[kLoads];
+  // Addresses: scalar base (steps along K) + 32-bit lane offset (fixed for the tile); see dma16s.
+  // The Mixtral forward tile draws its columns from two tensors: its B loads keep 64-bit lane addresses.
+  constexpr bool kBPtr = kGluFwd;
+  uint32_t va[kLoads], vb[kLoads];
   const unsigned char* gb[kLoads];
+  const unsigned char* sa;
+  const unsigned char* sb;
   int ka[kLoads], kb[kLoads];  // k-row inside the stage of this lane's slot (TR layouts)
   {
     const bf16_t* A = static_cast<const bf16_t*>(p.A[0]);
     const bf16_t* B0 = static_cast<const bf16_t*>(p.B[RAGGED_K ? t.set : 0]);
     const bf16_t* B1 = kGluFwd ? static_cast<const bf16_t*>(p.B[1]) : B0;
+    sa = to_sgpr(reinterpret_cast<const unsigned char*>(LA == KC ? A + (long)(t.r0 + t.mt * BM) * lda : A + (long)t.r0 * lda + t.mt * BM) - kDmaBias);
+    {
+      const long rowpart = (LB == TR && RAGGED_K) ? (long)t.r0 * ldb : (long)t.e * p.gB;
+      sb = to_sgpr(reinterpret_cast<const unsigned char*>(B0 + rowpart + (LB == KC ? (long)t.nt * BN * ldb : (long)t.nt * BN)) - kDmaBias);
+    }
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
       const int blk = wave * kLoads + j;
+      const uint32_t bias_a = (uint32_t)(kDmaBias - (-kPartBytes + 1024 * j)), bias_b = (uint32_t)(kDmaBias - 1024 * j);
       if (LA == KC) {  // 16 rows x 64 B per block; rows = output rows of this expert, clamped to its last row
         const int row = blk * 16 + (lane >> 2), slot = lane & 3;
         const int c = slot ^ ((row >> 2) & 3);
-        const int grow = t.r0 + min(t.mt * BM + row, t.rows - 1);
-        ga[j] = reinterpret_cast<const unsigned char*>(A + (long)grow * lda + c * 8);
+        const int rrow = min(t.mt * BM + row, t.rows - 1) - t.mt * BM;
+        va[j] = (uint32_t)rrow * (uint32_t)(lda * 2) + c * 16 + bias_a;
         ka[j] = 0;
       } else {  // 2 k-rows x 512 B per block; ragged K: [k][i], i = weight-gradient row, clamped to the matrix
         const int krow = blk * 2 + (lane >> 5), pos = lane & 31;
         const int seg = (pos >> 1) ^ tr_swz(krow);
-        const int i0 = min(t.mt * BM + (seg * 2 + (pos & 1)) * 8, p.Mfix - 8);
-        ga[j] = reinterpret_cast<const unsigned char*>(A + (long)(t.r0 + krow) * lda + i0);
+        const int ri = min(t.mt * BM + (seg * 2 + (pos & 1)) * 8, p.Mfix - 8) - t.mt * BM;
+        va[j] = (uint32_t)krow * (uint32_t)(lda * 2) + ri * 2 + bias_a;
         ka[j] = krow;
       }
+      vb[j] = 0;
+      gb[j] = nullptr;
       if (LB == KC) {  // rows = output columns n, k contiguous
         const int row = blk * 16 + (lane >> 2), slot = lane & 3;
         const int c = slot ^ ((row >> 2) & 3);
-        const int n = min(t.nt * BN + row, p.N - 1);
-        gb[j] = reinterpret_cast<const unsigned char*>(B0 + (long)t.e * p.gB + (long)n * ldb + c * 8);
+        const int rn = min(t.nt * BN + row, p.N - 1) - t.nt * BN;
+        vb[j] = (uint32_t)rn * (uint32_t)(ldb * 2) + c * 16 + bias_b;
         kb[j] = 0;
       } else {
         const int krow = blk * 2 + (lane >> 5), pos = lane & 31;
         const int seg = (pos >> 1) ^ tr_swz(krow);
         const int cc = seg * 2 + (pos & 1);  // 8-column chunk of the tile
-        int col;
-        const bf16_t* B = B0;
         if (kGluFwd) {  // tile columns: [wn][W1 64 | W3 64]
-          col = t.nt * kOutCols + (cc >> 4) * 64 + (cc & 7) * 8;
-          if ((cc >> 3) & 1) B = B1;
+          const int col = min(t.nt * kOutCols + (cc >> 4) * 64 + (cc & 7) * 8, p.N - 8);
+          const bf16_t* B = ((cc >> 3) & 1) ? B1 : B0;
+          gb[j] = reinterpret_cast<const unsigned char*>(B + (long)t.e * p.gB + (long)krow * ldb + col);
         } else {
-          col = t.nt * BN + cc * 8;
+          const int rcol = min(t.nt * BN + cc * 8, p.N - 8) - t.nt * BN;
+          vb[j] = (uint32_t)krow * (uint32_t)(ldb * 2) + rcol * 2 + bias_b;
         }
-        col = min(col, p.N - 8);
-        const long rowpart = RAGGED_K ? (long)(t.r0 + krow) * ldb : (long)t.e * p.gB + (long)krow * ldb;
-        gb[j] = reinterpret_cast<const unsigned char*>(B + rowpart + col);
         kb[j] = krow;
       }
     }
   }
   const long a_step = (LA == KC ? (long)BK : (long)BK * lda) * 2;  // bytes per K stage
   const long b_step = (LB == KC ? (long)BK : (long)BK * ldb) * 2;
-  // second operand pair of a summed product (dxe = da1.W1^T + da3.W3^T): jump of the pointers at it = nk1
+  // second operand pair of a summed product (dxe = da1.W1^T + da3.W3^T): jump of the bases at it = nk1
   const long a_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.A[1]) - reinterpret_cast<const unsigned char*>(p.A[0]) - nk1 * a_step : 0;
   const long b_jump = sum_pairs == 2 ? reinterpret_cast<const unsigned char*>(p.B[1]) - reinterpret_cast<const unsigned char*>(p.B[0]) - nk1 * b_step : 0;
 
   // Loads of K stage `it_load` into LDS stage S, one wave-level load per call (q = 0..7: A0 B0 A1 B1 ...);
-  // after the last one the pointers step to the next K stage.  Stages past the end re-fetch the last
+  // after the last one the bases step to the next K stage.  Stages past the end re-fetch the last
   // one (never read), so the number of loads in flight is the same in every iteration.
   int it_load = 0;
   auto issue_one = [&](auto stage_tag, int q) {
@@ -415,27 +445,28 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
     const int j = q >> 1;
     const bool is_b = q & 1;
     if (q == 0) dma_set_base(lds_addr_of(stage_a<S>()) + wave * kRegionBytes + kPartBytes);
-    if (RAGGED_K) {
-      // rows past the expert's last re-read its last row (finite data); the A rows are zeroed in
-      // LDS once they have landed (see iteration()), so those products vanish
-      const int k0 = it_load * BK;
-      if (is_b) {
-        const int over_b = max(0, k0 + kb[j] - (Kg - 1));
-        dma_block<true>(gb[j] - (long)over_b * ldb * 2, j);
-      } else {
-        const int over_a = max(0, k0 + ka[j] - (Kg - 1));
-        dma_block<false>(ga[j] - (long)over_a * lda * 2, j);
-      }
+    // ragged K: rows past the expert's last re-read its last row (finite data); the A rows are zeroed
+    // in LDS once they have landed (see iteration()), so those products vanish
+    const int k0 = it_load * BK;
+    if (is_b) {
+      const uint32_t back = RAGGED_K ? (uint32_t)max(0, k0 + kb[j] - (Kg - 1)) * (uint32_t)(ldb * 2) : 0u;
+      if (kBPtr) dma_block<true>(gb[j], j); else dma_block_s<true>(vb[j] - back, to_sgpr(sb), j);
     } else {
-      if (is_b) dma_block<true>(gb[j], j); else dma_block<false>(ga[j], j);
+      const uint32_t back = RAGGED_K ? (uint32_t)max(0, k0 + ka[j] - (Kg - 1)) * (uint32_t)(lda * 2) : 0u;
+      dma_block_s<false>(va[j] - back, to_sgpr(sa), j);
     }
     if (q == 2 * kLoads - 1) {
       const bool last = it_load + 1 >= nk;
       const bool jump = it_load + 1 == nk1 && sum_pairs == 2;
       const long da_ = last ? 0 : a_step + (jump ? a_jump : 0);
       const long db_ = last ? 0 : b_step + (jump ? b_jump : 0);
+      sa += da_;
+      if (kBPtr) {
 #pragma unroll
-      for (int u = 0; u < kLoads; ++u) { ga[u] += da_; gb[u] += db_; }
+        for (int u = 0; u < kLoads; ++u) gb[u] += db_;
+      } else {
+        sb += db_;
+      }
       it_load += last ? 0 : 1;
     }
   };
@@ -516,6 +547,9 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         for (int fn = 0; fn < 4; ++fn)
           acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[fn], ay[j], acc[j][fn], 0, 0, 0);
       }
+      // keep the region as written: left alone, the scheduler sinks the fragment reads down to
+      // their use and the matrix pipe waits out the LDS latency
+      __builtin_amdgcn_sched_barrier(0);
     }
     // Second half: this stage's second fragments (Y) under the MFMAs of X.
 #pragma unroll
@@ -531,6 +565,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
 #pragma unroll
       for (int fn = 0; fn < 4; ++fn)
         acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[fn], ax[j], acc[j][fn], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
@@ -595,17 +630,6 @@ __device__ __forceinline__ void dma_block8(const unsigned char* g, int q) {
     case 6: dma16<2048>(g); break;
     default: dma16<3072>(g); break;
   }
-}
-constexpr int kDmaBias = 4096;
-// a wave-uniform pointer the compiler may hold in vector registers (tile indices come out of
-// integer divisions, which run on the vector ALU) -> scalar registers
-__device__ __forceinline__ const unsigned char* to_sgpr(const unsigned char* p) {
-  const uint64_t v = reinterpret_cast<uint64_t>(p);
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-  return reinterpret_cast<const unsigned char*>(((uint64_t)hi << 32) | lo);
-}
-template <int OFF> __device__ __forceinline__ void dma16s(uint32_t voff, const unsigned char* sbase) {
-  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(sbase), "n"(OFF) : "memory");
 }
 __device__ __forceinline__ void dma_block8s(uint32_t voff, const unsigned char* sbase, int q) {
   switch (q) {
