@@ -619,18 +619,6 @@ template <int B> __device__ __forceinline__ unsigned char* batch_buf() {
   else if constexpr (B == 3) return g_st3; else return g_st4;
 }
 // load q (0..7) of a wave's 8 KB share of a batch; M0 points at the middle of that share
-__device__ __forceinline__ void dma_block8(const unsigned char* g, int q) {
-  switch (q) {
-    case 0: dma16<-4096>(g); break;
-    case 1: dma16<-3072>(g); break;
-    case 2: dma16<-2048>(g); break;
-    case 3: dma16<-1024>(g); break;
-    case 4: dma16<0>(g); break;
-    case 5: dma16<1024>(g); break;
-    case 6: dma16<2048>(g); break;
-    default: dma16<3072>(g); break;
-  }
-}
 __device__ __forceinline__ void dma_block8s(uint32_t voff, const unsigned char* sbase, int q) {
   switch (q) {
     case 0: dma16s<-4096>(voff, sbase); break;
@@ -654,14 +642,18 @@ __device__ __forceinline__ bf16x8 read_kc64(const unsigned char* op, int row0, i
   const int c = 2 * ks + (lane >> 5);
   return *reinterpret_cast<const bf16x8*>(op + row * 128 + ((c ^ kc64_swz(row)) << 4));
 }
-// row-major batch: k-row k at k * 512, segments swizzled as in the 32-k stages
+// row-major batch: k-row k at k * PITCH, segments swizzled as in the 32-k stages.  PITCH 512: one
+// tensor, 256 columns.  PITCH 256: the Mixtral forward tile, whose batch is two halves of 16 KB,
+// [64 k][128 columns of W1] then [64 k][128 columns of W3], so that a wave-level load (4 k-rows x
+// 256 bytes) draws on one tensor and can take the scalar-base form.
+template <int PITCH>
 __device__ __forceinline__ bf16x8 read_tr64(const unsigned char* op, int col0, int ks, int lane) {
   const int grp = lane >> 4, i = lane & 15;
   const int seg = (col0 >> 4) + (grp & 1);
   const int k = 16 * ks + 8 * (grp >> 1) + (i >> 2);
-  const int a0 = k * 512 + ((seg ^ tr_swz(k)) << 5) + ((i & 3) << 3);
+  const int a0 = k * PITCH + ((seg ^ tr_swz(k)) << 5) + ((i & 3) << 3);
   const int k1 = k + 4;
-  const int a1 = k1 * 512 + ((seg ^ tr_swz(k1)) << 5) + ((i & 3) << 3);
+  const int a1 = k1 * PITCH + ((seg ^ tr_swz(k1)) << 5) + ((i & 3) << 3);
   typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(op + a0));
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(op + a1));
@@ -693,19 +685,17 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
   // meanwhile: about 18 cycles with a 64-bit address per lane, about 3 with a 32-bit offset (measured).
   // The instruction adds its immediate offset to the LDS address and to the global address alike, so
   // the lane offset carries kDmaBias - OFF and the scalar base is kDmaBias short.
-  // The Mixtral forward tile takes its columns from two tensors (W1 | W3): those loads keep a full
-  // address per lane.
-  constexpr bool kBPtr = kGluFwd;  // B loads with per-lane 64-bit addresses
   uint32_t va[8], vb[8];
-  const unsigned char* gb[8];
   const unsigned char* sa;
   const unsigned char* sb;
+  const unsigned char* sb3;  // Mixtral forward: W3 (sb is W1)
   {
     const bf16_t* A = static_cast<const bf16_t*>(p.A[0]);
     const bf16_t* B0 = static_cast<const bf16_t*>(p.B[0]);
     const bf16_t* B1 = kGluFwd ? static_cast<const bf16_t*>(p.B[1]) : B0;
     sa = to_sgpr(reinterpret_cast<const unsigned char*>(A + (long)(t.r0 + t.mt * BM) * lda) - kDmaBias);
-    sb = to_sgpr(reinterpret_cast<const unsigned char*>(B0 + (long)t.e * p.gB + (LB == KC ? (long)t.nt * BN * ldb : (long)t.nt * BN)) - kDmaBias);
+    sb = to_sgpr(reinterpret_cast<const unsigned char*>(B0 + (long)t.e * p.gB + (LB == KC ? (long)t.nt * BN * ldb : (long)t.nt * kOutCols)) - kDmaBias);
+    sb3 = to_sgpr(reinterpret_cast<const unsigned char*>(B1 + (long)t.e * p.gB + (long)t.nt * kOutCols) - kDmaBias);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const uint32_t bias = (uint32_t)(kDmaBias - (-4096 + 1024 * j));
@@ -715,22 +705,19 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
       const int rrow = min(t.mt * BM + row, t.rows - 1) - t.mt * BM;  // rows past the expert's last re-read it
       va[j] = (uint32_t)rrow * (uint32_t)(lda * 2) + c * 16 + bias;
       vb[j] = 0;
-      gb[j] = nullptr;
       if (LB == KC) {
         const int rn = min(t.nt * BN + row, p.N - 1) - t.nt * BN;
         vb[j] = (uint32_t)rn * (uint32_t)(ldb * 2) + c * 16 + bias;
+      } else if (kGluFwd) {  // load j of half j / 4 = k-rows 16 wave + 4 (j % 4) .. + 3; lane i -> (k-row i / 16, slot i % 16)
+        const int krow = wave * 16 + (j & 3) * 4 + (lane >> 4), pos = lane & 15;
+        const int seg = (pos >> 1) ^ tr_swz(krow);
+        const int rcol = min(t.nt * kOutCols + (seg * 2 + (pos & 1)) * 8, p.N - 8) - t.nt * kOutCols;
+        vb[j] = (uint32_t)krow * (uint32_t)(ldb * 2) + rcol * 2 + (uint32_t)(kDmaBias - (-2048 + 1024 * (j & 3)));
       } else {  // row-major: load j = k-rows 16 wave + 2 j, + 1; lane i -> (k-row i / 32, 16-byte slot i % 32)
         const int krow = wave * 16 + j * 2 + (lane >> 5), pos = lane & 31;
         const int seg = (pos >> 1) ^ tr_swz(krow);
-        const int cc = seg * 2 + (pos & 1);  // 8-column chunk of the tile
-        if (kGluFwd) {  // tile columns: [wn][W1 64 | W3 64]
-          const int col = min(t.nt * kOutCols + (cc >> 4) * 64 + (cc & 7) * 8, p.N - 8);
-          const bf16_t* B = ((cc >> 3) & 1) ? B1 : B0;
-          gb[j] = reinterpret_cast<const unsigned char*>(B + (long)t.e * p.gB + (long)krow * ldb + col);
-        } else {
-          const int rcol = min(t.nt * BN + cc * 8, p.N - 8) - t.nt * BN;
-          vb[j] = (uint32_t)krow * (uint32_t)(ldb * 2) + rcol * 2 + bias;
-        }
+        const int rcol = min(t.nt * BN + (seg * 2 + (pos & 1)) * 8, p.N - 8) - t.nt * BN;
+        vb[j] = (uint32_t)krow * (uint32_t)(ldb * 2) + rcol * 2 + bias;
       }
     }
   }
@@ -755,17 +742,24 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
   };
   auto issue_b = [&](auto buf_tag, int q) {
     constexpr int BUF = decltype(buf_tag)::value;
-    if (q == 0) dma_set_base(lds_addr_of(batch_buf<BUF>()) + wave * 8192 + 4096);
-    if (kBPtr) dma_block8(gb[q], q); else dma_block8s(vb[q], to_sgpr(sb), q);
+    if (kGluFwd) {
+      if ((q & 3) == 0) dma_set_base(lds_addr_of(batch_buf<BUF>()) + (q >> 2) * (kBatchBytes / 2) + wave * 4096 + 2048);
+      const unsigned char* base = to_sgpr(q < 4 ? sb : sb3);
+      switch (q & 3) {
+        case 0: dma16s<-2048>(vb[q], base); break;
+        case 1: dma16s<-1024>(vb[q], base); break;
+        case 2: dma16s<0>(vb[q], base); break;
+        default: dma16s<1024>(vb[q], base); break;
+      }
+    } else {
+      if (q == 0) dma_set_base(lds_addr_of(batch_buf<BUF>()) + wave * 8192 + 4096);
+      dma_block8s(vb[q], to_sgpr(sb), q);
+    }
     if (q == 7) {
       const bool last = ib + 1 >= nb;
       const long d = last ? 0 : b_step + ((ib + 1 == nb1 && sum_pairs == 2) ? b_jump : 0);
-      if (kBPtr) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u) gb[u] += d;
-      } else {
-        sb += d;
-      }
+      sb += d;
+      sb3 += d;
       ib += last ? 0 : 1;
     }
   };
@@ -781,7 +775,9 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
   bf16x8 ax[4], bx[4], ay[4], by[4];  // fragment sets X (first 16 k of a half-step) and Y (second 16 k)
   auto frag_a = [&](const unsigned char* buf, int f, int ks) { return read_kc64(buf, wm * 128 + f * 32, ks, lane); };
   auto frag_b = [&](const unsigned char* buf, int f, int ks) {
-    return LB == KC ? read_kc64(buf, wn * 128 + f * 32, ks, lane) : read_tr64(buf, wn * 128 + f * 32, ks, lane);
+    if (LB == KC) return read_kc64(buf, wn * 128 + f * 32, ks, lane);
+    if (kGluFwd) return read_tr64<256>(buf + (f >> 1) * (kBatchBytes / 2), wn * 64 + (f & 1) * 32, ks, lane);
+    return read_tr64<512>(buf, wn * 128 + f * 32, ks, lane);
   };
 
   // Half-step PH of the ten in a period: 64-k step U = PH / 2 of five, half H = PH % 2.
