@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per step of the six expert-GEMM launches at the Mixtral shape, from the rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gg_mfma_kernel_mixtral_hbm_traffic.md (scaled by
 # the factors a plain 1 GiB copy gives: 2.0 and 1.0).  Algorithmic bytes for the same launches: 22.3e9.
-MEASURED_GEMM_TRAFFIC = {"mixtral": {"read": 68.2e9, "written": 11.8e9}}
+MEASURED_GEMM_TRAFFIC = {"mixtral": {"read": 64.3e9, "written": 8.1e9}}
 
 
 def parse():
@@ -36,9 +36,39 @@ def parse():
     ap.add_argument("--workload", default="mixtral", choices=["tiny", "gpt2", "mixtral", "finegrained", "switch"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--calibrate-gemm", action="store_true",
+                    help="also time the vendor library's plain bf16 GEMM (torch.matmul) for about a second per layout on this box: "
+                         "context for the MFMA roofline fraction, since the sustained clock differs from box to box")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3 byte counters)")
     return ap.parse_args()
+
+
+def library_gemm_reference(torch, m=32768, n=4096, k=14336, secs=1.0):
+    """Sustained TFLOP/s of torch.matmul (hipBLASLt) in bf16 on one dense product of the size of the Mixtral
+    q = hh.W2 product with all experts merged; B row-major [k,n] ("NN") and B = W^T with W [n,k] ("NT")."""
+    a = torch.randn(m, k, device="cuda", dtype=torch.bfloat16)
+    out = {}
+    for name in ("NN", "NT"):
+        b = torch.randn((k, n) if name == "NN" else (n, k), device="cuda", dtype=torch.bfloat16) * 0.02
+        bb = b if name == "NN" else b.t()
+        c = torch.empty(m, n, device="cuda", dtype=torch.bfloat16)
+        torch.matmul(a, bb, out=c)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rates = []
+        while time.perf_counter() - t0 < secs:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                torch.matmul(a, bb, out=c)
+            e1.record()
+            torch.cuda.synchronize()
+            rates.append(2.0 * m * n * k * 10 / e0.elapsed_time(e1) / 1e9)
+        half = rates[len(rates) // 2:]
+        out[name] = round(sum(half) / len(half), 1)
+        del b, bb, c
+    return {"what": f"torch.matmul bf16 {m}x{n}x{k}, sustained, TFLOP/s", **out}
 
 
 def device_inputs(w, torch):
@@ -92,6 +122,9 @@ def main():
         moe.moe_layer_bwd(cfg, d["dy"], d["x"], d["w_gate"], d["w1"], d["w3"], d["w2"], b.saved, b.dx, b.dw_gate,
                           b.db_gate if has_bias else None, b.dw1, b.dw3, b.dw2, b.ws)
 
+    library_gemm = None
+    if args.calibrate_gemm:
+        library_gemm = library_gemm_reference(torch)
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -138,7 +171,7 @@ def main():
                                                      b.dxe, b.dw1, b.dw3, b.dw2, b.ws), reps)
     gemm_ms = t_ffn_fwd + t_ffn_bwd
     achieved = (flop_fwd + flop_bwd) / (gemm_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gg_mfma_kernel (bf16 grouped GEMM, 2 forward + 4 backward launches per step)",
+    roofline = {"bound": "mfma", "kernel": "gg_mfma64_kernel / gg_mfma_kernel (bf16 grouped GEMM, 2 forward + 4 backward launches per step)",
                 "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": (lambda t: None if t is None else t["read"] + t["written"])(MEASURED_GEMM_TRAFFIC.get(w.name)),
@@ -154,6 +187,8 @@ def main():
                w.name, w.N, w.M, w.E, w.H, w.k, S.capacity_factor_text(w), w.act, w.renormalize, w.add_residual),
                "kept_rows": A, "rows_per_expert_min_max": [int(count.min()), int(count.max())]},
            "expert_gemm_tflops": round(achieved, 1), "roofline": roofline}
+    if library_gemm is not None:
+        out["library_gemm_reference"] = library_gemm
 
     if not args.no_breakdown:
         bpe = 2 if w.dtype == S.DT_BF16 else 4
