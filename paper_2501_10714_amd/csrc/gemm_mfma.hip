@@ -4,18 +4,22 @@
 // One workgroup (256 lanes = 4 waves, one per SIMD) owns a 256x256 output tile.  Each wave owns a
 // 128x128 quadrant = 4x4 MFMA 32x32x16 tiles, fp32 accumulators (256 registers per lane).
 //
-// K pipeline: four LDS stages of 32 k (16 KB per operand per stage, 128 KB in all).  Tiles travel
-// global -> LDS directly (global_load_lds_dwordx4, no registers, no ds_write); while stage i is
-// multiplied, stages i+1..i+3 are in flight, so about three stage-times of memory latency are
-// covered.  A wave-level load drops 64 x 16 bytes into 1 KB of contiguous LDS, so the bank swizzle
-// is applied on the global side: each lane fetches the chunk that belongs at its LDS slot.
-// The stages are separate __shared__ arrays and the K loop is unrolled by four, so every LDS access
-// names its stage statically; the compiler then knows a fragment read of one stage does not have to
-// wait for the loads that are filling another.
-// Fragments are double buffered across the barrier: the MFMAs of the second half of stage i-1 run
-// while the first fragments of stage i are read.
+// Operands travel global -> LDS directly (global_load_lds_dwordx4: no registers, no ds_write).  A
+// wave-level load drops 64 x 16 bytes into 1 KB of contiguous LDS, so the bank swizzle is applied on
+// the global side: each lane fetches the chunk that belongs at its LDS slot.  Two K pipelines:
 //
-// Operand layouts in LDS (bf16):
+//   gg_mfma_kernel    four LDS stages of 32 k (32 KB each), three in flight, one barrier per 32 k.
+//                     Used by the weight-gradient products (both operands row-major, K = the ragged
+//                     expert rows) and by any product whose K is not a multiple of 64.
+//   gg_mfma64_kernel  64-k batches in a ring of five 32 KB buffers, one barrier per 64 k (described
+//                     at its definition).  Used when the A operand is K-contiguous and K % 64 == 0:
+//                     a K-contiguous operand then arrives in whole 128-byte cache lines.
+//
+// In both, the buffers are separate __shared__ arrays and the K loop is unrolled over a full turn
+// of the ring, so every LDS access names its buffer statically; fragments are double buffered in
+// registers (the MFMAs of one 16-k step run while the fragments of the next are read).
+//
+// Operand layouts in LDS (bf16), 32-k stages:
 //   KC  "K-contiguous rows"  [256 rows][32 k]   64-byte rows, 16-byte chunks XOR-swizzled by row.
 //        A lane reads its 8 consecutive k of one row with one ds_read_b128.
 //   TR  "transposed feed"    [32 k][256 cols]   512-byte rows, 32-byte segments XOR-swizzled by k.
@@ -29,11 +33,9 @@
 // output COLUMNS of one output row per accumulator quad; the epilogue turns the quadrant row-major
 // through LDS so that global stores (and the loads of the saved activations) are full cache lines.
 //
-// Tile order: hardware deals workgroup ids round-robin to the 8 XCDs (each with its own L2), so
-// id -> (xcd, slot) is remapped to give every XCD a contiguous range of logical tiles; inside that
-// range tiles are ordered in bands of 8 row-tiles x all column-tiles so the 32 CUs of an XCD share
-// A and B panels in L2.  Rows are ragged per expert: the tile list is derived from offsets[] on
-// the device by every workgroup (E <= 256 scalar steps), no host synchronisation.
+// Tile order: tiles are ordered per expert in bands of 8 row-tiles x all column-tiles and dealt to
+// the 8 XCDs in chunks of 32 (see find_tile).  Rows are ragged per expert: the tile list is derived
+// from offsets[] on the device by every workgroup (E <= 256 scalar steps), no host synchronisation.
 #include <cstdlib>
 #include <type_traits>
 
@@ -55,6 +57,7 @@ constexpr int kThreads = 256;
 constexpr int kStages = 4;
 constexpr int kOpBytes = BM * BK * 2;  // 16 KB: one operand, one stage
 constexpr int kBand = 8;               // row-tiles per L2 band
+constexpr int kChunk = 32;             // consecutive logical tiles per XCD turn
 constexpr int kLoads = kOpBytes / 1024 / 4;  // wave-level 1 KB loads per wave per operand per stage (4)
 constexpr int kPartBytes = kLoads * 1024;    // one wave's share of one operand of one stage (4 KB)
 constexpr int kRegionBytes = 2 * kPartBytes; // a stage is four wave regions [A part | B part]
@@ -194,11 +197,12 @@ __device__ __forceinline__ TileId find_tile(const GemmP& p, int n_nt, int mt_fix
   } else {
     for (int e = 0; e < p.n_experts; ++e) total += ((p.offsets[e + 1] - p.offsets[e] + BM - 1) / BM) * n_nt;
   }
-  // XCD-aware remap: workgroup id b runs on XCD b % 8; give XCD x the logical range [x*per, (x+1)*per)
-  const int per = (total + 7) >> 3;
+  // XCD-aware remap: workgroup id b runs on XCD b % 8 (each XCD has its own L2).  Logical tiles are dealt
+  // to the XCDs in chunks of 32 consecutive ones (= 8 row tiles x 4 column tiles, one per CU of an XCD):
+  // inside an XCD the 32 tiles share A and B panels in its L2, and the 8 chunks in flight across the chip
+  // are neighbours in the same band, so they share their A panels in the memory-side cache.
   const int slot = blockIdx.x >> 3;
-  if (slot >= per) return t;
-  int L = (blockIdx.x & 7) * per + slot;
+  int L = (((slot / kChunk) << 3) + (blockIdx.x & 7)) * kChunk + (slot % kChunk);
   if (L >= total) return t;
   int g = 0, mt_g = mt_fix;
   if (RAGGED_K) {
@@ -872,7 +876,7 @@ moe_status_t launch_cfg64(const GemmP& p, hipStream_t s) {
   if (rows_bound > p.total_rows_bound) rows_bound = p.total_rows_bound;
   const int max_tiles = (int)((rows_bound + BM - 1) / BM + p.n_experts) * n_nt;
   if (max_tiles <= 0) return MOE_OK;
-  const int grid = ceil_div(max_tiles, 8) * 8;
+  const int grid = ceil_div(max_tiles, 8 * kChunk) * 8 * kChunk;  // whole turns of the XCD deal
   hipLaunchKernelGGL((gg_mfma64_kernel<LB, EPI, ACT>), dim3(grid), dim3(kThreads), 0, s, p, n_nt);
   MOE_CHECK_LAUNCH();
   return MOE_OK;
@@ -894,7 +898,7 @@ moe_status_t launch_cfg(const GemmP& p, hipStream_t s) {
   }
   if (max_tiles <= 0) return MOE_OK;
   auto kern = gg_mfma_kernel<LA, LB, EPI, RAGGED_K, ACT>;
-  const int grid = ceil_div(max_tiles, 8) * 8;  // the XCD remap wants a multiple of 8
+  const int grid = ceil_div(max_tiles, 8 * kChunk) * 8 * kChunk;  // whole turns of the XCD deal
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), 0, s, p, n_nt, mt_fix);
   MOE_CHECK_LAUNCH();
   return MOE_OK;
