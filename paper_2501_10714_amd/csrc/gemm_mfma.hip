@@ -186,24 +186,20 @@ struct TileId {
 
 // Logical tile index -> (expert, row tile, column tile).  Ragged M: row tiles per expert come from
 // offsets[]; ragged K: every group has the same mt_fix row tiles.
+// Number of output tiles of a launch.  Ragged M: row tiles per expert come from offsets[]; ragged K: every
+// group has the same mt_fix row tiles.
 template <bool RAGGED_K>
-__device__ __forceinline__ TileId find_tile(const GemmP& p, int n_nt, int mt_fix) {
-  TileId t;
-  t.valid = false;
-  const int groups = (RAGGED_K && p.n_pairs == 2) ? 2 * p.n_experts : p.n_experts;
+__device__ __forceinline__ int count_tiles(const GemmP& p, int n_nt, int mt_fix) {
+  if (RAGGED_K) return ((p.n_pairs == 2) ? 2 * p.n_experts : p.n_experts) * mt_fix * n_nt;
   int total = 0;
-  if (RAGGED_K) {
-    total = groups * mt_fix * n_nt;
-  } else {
-    for (int e = 0; e < p.n_experts; ++e) total += ((p.offsets[e + 1] - p.offsets[e] + BM - 1) / BM) * n_nt;
-  }
-  // XCD-aware remap: workgroup id b runs on XCD b % 8 (each XCD has its own L2).  Logical tiles are dealt
-  // to the XCDs in chunks of 32 consecutive ones (= 8 row tiles x 4 column tiles, one per CU of an XCD):
-  // inside an XCD the 32 tiles share A and B panels in its L2, and the 8 chunks in flight across the chip
-  // are neighbours in the same band, so they share their A panels in the memory-side cache.
-  const int slot = blockIdx.x >> 3;
-  int L = (((slot / kChunk) << 3) + (blockIdx.x & 7)) * kChunk + (slot % kChunk);
-  if (L >= total) return t;
+  for (int e = 0; e < p.n_experts; ++e) total += ((p.offsets[e + 1] - p.offsets[e] + BM - 1) / BM) * n_nt;
+  return total;
+}
+// Logical tile index L < count_tiles() -> (expert, row tile, column tile): per expert, bands of kBand
+// row tiles x all column tiles, row tile fastest inside a band.
+template <bool RAGGED_K>
+__device__ __forceinline__ TileId tile_at(const GemmP& p, int n_nt, int mt_fix, int L) {
+  TileId t;
   int g = 0, mt_g = mt_fix;
   if (RAGGED_K) {
     g = L / (mt_fix * n_nt);
@@ -228,22 +224,39 @@ __device__ __forceinline__ TileId find_tile(const GemmP& p, int n_nt, int mt_fix
   t.valid = true;
   return t;
 }
+// XCD-aware deal: workgroup id b runs on XCD b % 8 (each XCD has its own L2).  Logical tiles are dealt to
+// the XCDs in chunks of `chunk` consecutive ones (32 = 8 row tiles x 4 column tiles, one per CU of an XCD):
+// inside an XCD the tiles of a chunk share A and B panels in its L2, and the 8 chunks in flight across the
+// chip are neighbours in the same band, so they share their A panels in the memory-side cache.
+__device__ __forceinline__ int dealt_tile(int slot, int chunk) {
+  return (((slot / chunk) << 3) + (blockIdx.x & 7)) * chunk + (slot % chunk);
+}
+template <bool RAGGED_K>
+__device__ __forceinline__ TileId find_tile(const GemmP& p, int n_nt, int mt_fix) {
+  const int L = dealt_tile(blockIdx.x >> 3, kChunk);
+  if (L >= count_tiles<RAGGED_K>(p, n_nt, mt_fix)) {
+    TileId t;
+    t.valid = false;
+    return t;
+  }
+  return tile_at<RAGGED_K>(p, n_nt, mt_fix, L);
+}
 
 // ---- epilogue.  In the accumulators a lane holds 4 consecutive columns of 32 different rows
 // (acc[fm][fn][4 rg + j] = C[wm*128 + fm*32 + lane%32][wn*128 + fn*32 + rg*8 + (lane/32)*4 + j]);
 // stored like that, every store instruction would scatter 16-byte pieces over 32 rows and the L2
-// write path would set the pace.  Each wave therefore passes its quadrant through its own 32 KB of
-// the (now idle) LDS, 32 rows at a time in fp32, and reads it back row-major: a lane then owns 8
-// consecutive columns, 16 lanes cover 256 contiguous bytes of a row, and all global loads and
-// stores of the fused epilogues are 16-byte vectors on full cache lines.
-// Must be entered by all four waves; waits for every outstanding direct-to-LDS load first.
+// write path would set the pace.  Each wave therefore passes its quadrant through 16 KB of LDS of its
+// own (`scr`), 32 rows at a time in fp32, and reads it back row-major: a lane then owns 8 consecutive
+// columns, 16 lanes cover 256 contiguous bytes of a row, and all global loads and stores of the fused
+// epilogues are 16-byte vectors on full cache lines.  Scratch row r (128 floats) keeps 16-byte chunk q
+// at slot q ^ r: column writes (32 rows, one chunk) and row reads (one row, 16 chunks) both touch every
+// bank once.  The caller makes sure that no wave still reads, and no load still fills, that LDS.
 template <int EPI, bool RAGGED_K, int ACT>
-__device__ __forceinline__ void tile_epilogue(const GemmP& p, const TileId& t, f32x16 (&acc)[4][4], int wave, int lane) {
+__device__ __forceinline__ void tile_epilogue(const GemmP& p, const TileId& t, f32x16 (&acc)[4][4], float* scr, int wave, int lane) {
   constexpr bool kGluFwd = EPI == EPI_GLU_FWD;
   constexpr int kOutCols = kGluFwd ? BN / 2 : BN;
   const int wm = wave >> 1, wn = wave & 1;
-  float* scr = reinterpret_cast<float*>(wave == 0 ? g_st0 : wave == 1 ? g_st1 : wave == 2 ? g_st2 : g_st3);
-  constexpr int kPitch = 128 + 4;  // floats per scratch row (+16 bytes: conflict-free 16-byte column writes)
+  auto scr_at = [&](int r, int q) { return scr + r * 128 + ((q ^ r) << 2); };  // row r (0..31), 16-byte chunk q (0..31)
   const int m_limit = RAGGED_K ? p.Mfix : t.rows;
   constexpr int kLanesPerRow = kGluFwd ? 8 : 16;   // 8 columns per lane
   constexpr int kRowsPerPass = 64 / kLanesPerRow;
@@ -279,8 +292,6 @@ __device__ __forceinline__ void tile_epilogue(const GemmP& p, const TileId& t, f
     }
   };
   prefetch(0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end have landed
-  __syncthreads();                                  // every wave is done with the K stages
 #pragma unroll
   for (int fm = 0; fm < 4; ++fm) {
     if (fm + 1 < 4) prefetch(fm + 1);
@@ -289,7 +300,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmP& p, const TileId& t, f
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
         f32x4 v = {acc[fm][fn][4 * rg], acc[fm][fn][4 * rg + 1], acc[fm][fn][4 * rg + 2], acc[fm][fn][4 * rg + 3]};
-        *reinterpret_cast<f32x4*>(scr + (lane & 31) * kPitch + fn * 32 + rg * 8 + (lane >> 5) * 4) = v;
+        *reinterpret_cast<f32x4*>(scr_at(lane & 31, fn * 8 + rg * 2 + (lane >> 5))) = v;
       }
 #pragma unroll
     for (int ps = 0; ps < kPasses; ++ps) {
@@ -297,15 +308,15 @@ __device__ __forceinline__ void tile_epilogue(const GemmP& p, const TileId& t, f
       const int mrow = t.mt * BM + wm * 128 + fm * 32 + r;  // row inside the group
       float v[8];
       {
-        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr + r * kPitch + c8);
-        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr + r * kPitch + c8 + 4);
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr_at(r, c8 >> 2));
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr_at(r, (c8 >> 2) + 1));
 #pragma unroll
         for (int j = 0; j < 4; ++j) { v[j] = lo[j]; v[4 + j] = hi[j]; }
       }
       float g[8];
       if (kGluFwd) {
-        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr + r * kPitch + 64 + c8);
-        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr + r * kPitch + 64 + c8 + 4);
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(scr_at(r, 16 + (c8 >> 2)));
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(scr_at(r, 17 + (c8 >> 2)));
 #pragma unroll
         for (int j = 0; j < 4; ++j) { g[j] = lo[j]; g[4 + j] = hi[j]; }
       }
@@ -592,7 +603,9 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end must land before the LDS goes back to the pool
   }
 
-  tile_epilogue<EPI, RAGGED_K, ACT>(p, t, acc, wave, lane);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the re-fetches past the end have landed
+  __syncthreads();                                  // every wave is done with the K stages
+  tile_epilogue<EPI, RAGGED_K, ACT>(p, t, acc, reinterpret_cast<float*>(wave == 0 ? g_st0 : wave == 1 ? g_st1 : wave == 2 ? g_st2 : g_st3), wave, lane);
 }
 
 // ============================================================================================
@@ -865,7 +878,9 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
         acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[fn], ay[fm], acc[fm][fn], 0, 0, 0);
   }
 #undef MOE_HS
-  tile_epilogue<EPI, false, ACT>(p, t, acc, wave, lane);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  tile_epilogue<EPI, false, ACT>(p, t, acc, reinterpret_cast<float*>(wave == 0 ? g_st0 : wave == 1 ? g_st1 : wave == 2 ? g_st2 : g_st3), wave, lane);
 }
 
 template <int LB, int EPI, int ACT = 0>
