@@ -394,7 +394,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
   const unsigned char* gb[kLoads];
   const unsigned char* sa;
   const unsigned char* sb;
-  int ka[kLoads], kb[kLoads];  // k-row inside the stage of this lane's slot (TR layouts)
+  int ka[kLoads], kb[kLoads];  // row-major layouts: byte offset of this lane's k-row inside the stage (k-row * row pitch)
   {
     const bf16_t* A = static_cast<const bf16_t*>(p.A[0]);
     const bf16_t* B0 = static_cast<const bf16_t*>(p.B[RAGGED_K ? t.set : 0]);
@@ -418,8 +418,8 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
         const int krow = blk * 2 + (lane >> 5), pos = lane & 31;
         const int seg = (pos >> 1) ^ tr_swz(krow);
         const int ri = min(t.mt * BM + (seg * 2 + (pos & 1)) * 8, p.Mfix - 8) - t.mt * BM;
-        va[j] = (uint32_t)krow * (uint32_t)(lda * 2) + ri * 2 + bias_a;
-        ka[j] = krow;
+        va[j] = ri * 2 + bias_a;  // + the k-row part, added per load (clamped at the expert's last row)
+        ka[j] = krow * (int)(lda * 2);
       }
       vb[j] = 0;
       gb[j] = nullptr;
@@ -439,9 +439,9 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
           gb[j] = reinterpret_cast<const unsigned char*>(B + (long)t.e * p.gB + (long)krow * ldb + col);
         } else {
           const int rcol = min(t.nt * BN + cc * 8, p.N - 8) - t.nt * BN;
-          vb[j] = (uint32_t)krow * (uint32_t)(ldb * 2) + rcol * 2 + bias_b;
+          vb[j] = rcol * 2 + bias_b;
         }
-        kb[j] = krow;
+        kb[j] = krow * (int)(ldb * 2);
       }
     }
   }
@@ -461,14 +461,14 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
     const bool is_b = q & 1;
     if (q == 0) dma_set_base(lds_addr_of(stage_a<S>()) + wave * kRegionBytes + kPartBytes);
     // ragged K: rows past the expert's last re-read its last row (finite data); the A rows are zeroed
-    // in LDS once they have landed (see iteration()), so those products vanish
-    const int k0 = it_load * BK;
+    // in LDS once they have landed (see iteration()), so those products vanish.  The clamp is one
+    // v_min against a scalar: min(k-row, last row of the expert inside this stage) * row pitch.
+    const int last_row = RAGGED_K ? min(Kg - 1 - it_load * BK, BK) : BK;  // >= 0: stages past the end re-fetch the last one
     if (is_b) {
-      const uint32_t back = RAGGED_K ? (uint32_t)max(0, k0 + kb[j] - (Kg - 1)) * (uint32_t)(ldb * 2) : 0u;
-      if (kBPtr) dma_block<true>(gb[j], j); else dma_block_s<true>(vb[j] - back, to_sgpr(sb), j);
+      if (kBPtr) dma_block<true>(gb[j], j);
+      else dma_block_s<true>(vb[j] + (LB == TR ? (uint32_t)min(kb[j], last_row * (int)(ldb * 2)) : 0u), to_sgpr(sb), j);
     } else {
-      const uint32_t back = RAGGED_K ? (uint32_t)max(0, k0 + ka[j] - (Kg - 1)) * (uint32_t)(lda * 2) : 0u;
-      dma_block_s<false>(va[j] - back, to_sgpr(sa), j);
+      dma_block_s<false>(va[j] + (LA == TR ? (uint32_t)min(ka[j], last_row * (int)(lda * 2)) : 0u), to_sgpr(sa), j);
     }
     if (q == 2 * kLoads - 1) {
       const bool last = it_load + 1 >= nk;
@@ -535,7 +535,7 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
       if (it_cur == nk - 1 && (Kg & (BK - 1)) != 0) {  // ragged K tail: zero the A rows past the expert's last
 #pragma unroll
         for (int j = 0; j < kLoads; ++j)
-          if (it_cur * BK + ka[j] >= Kg)
+          if (it_cur * BK + (wave * kLoads + j) * 2 + (lane >> 5) >= Kg)
             *reinterpret_cast<u32x4*>(stage_a<S>() + wave * kRegionBytes + j * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
         __syncthreads();
       }
