@@ -548,38 +548,40 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
     // First half: this stage's first fragments (X) under the MFMAs of the previous stage's second half (Y).
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      // B fragments first: the first MFMA on X needs all four of them, but only ax[0].
+      // One MFMA, then at most one fragment read (1-2 LDS instructions) or one load: a wave has a
+      // single instruction stream, and a run of other instructions between two MFMAs that lasts
+      // longer than the 32 cycles of an MFMA leaves the matrix pipe idle.  The scheduler is held
+      // to this order (sched_barrier): left alone it sinks the reads down to their use.
+      if (j < 2) bx[2 * j] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j) * 32, 0, lane);
+      else ax[2 * j - 4] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 4) * 32, 0, lane);
+      if (!kFirst) acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[0], ay[j], acc[j][0], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (j < 2) bx[2 * j + 1] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j + 1) * 32, 0, lane);
+      else ax[2 * j - 3] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 3) * 32, 0, lane);
+      if (!kFirst) acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[1], ay[j], acc[j][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       issue_one(std::integral_constant<int, (S + 3) % kStages>{}, j);
-      // B fragments first: the first MFMA on X needs all four of them, but only ax[0]
-      if (j < 2) {
-        bx[2 * j] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j) * 32, 0, lane);
-        bx[2 * j + 1] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j + 1) * 32, 0, lane);
-      } else {
-        ax[2 * j - 4] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 4) * 32, 0, lane);
-        ax[2 * j - 3] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 3) * 32, 0, lane);
-      }
-      if (!kFirst) {
-#pragma unroll
-        for (int fn = 0; fn < 4; ++fn)
-          acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[fn], ay[j], acc[j][fn], 0, 0, 0);
-      }
-      // keep the region as written: left alone, the scheduler sinks the fragment reads down to
-      // their use and the matrix pipe waits out the LDS latency
+      if (!kFirst) acc[j][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[2], ay[j], acc[j][2], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!kFirst) acc[j][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[3], ay[j], acc[j][3], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
     // Second half: this stage's second fragments (Y) under the MFMAs of X.
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      if (j < 2) by[2 * j] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j) * 32, 1, lane);
+      else ay[2 * j - 4] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 4) * 32, 1, lane);
+      acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[0], ax[j], acc[j][0], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (j < 2) by[2 * j + 1] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j + 1) * 32, 1, lane);
+      else ay[2 * j - 3] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 3) * 32, 1, lane);
+      acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[1], ax[j], acc[j][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       issue_one(std::integral_constant<int, (S + 3) % kStages>{}, 4 + j);
-      if (j < 2) {
-        by[2 * j] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j) * 32, 1, lane);
-        by[2 * j + 1] = read_frag<LB>(stage_b<S>(), wn * 128 + (2 * j + 1) * 32, 1, lane);
-      } else {
-        ay[2 * j - 4] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 4) * 32, 1, lane);
-        ay[2 * j - 3] = read_frag<LA>(stage_a<S>(), wm * 128 + (2 * j - 3) * 32, 1, lane);
-      }
-#pragma unroll
-      for (int fn = 0; fn < 4; ++fn)
-        acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[fn], ax[j], acc[j][fn], 0, 0, 0);
+      acc[j][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[2], ax[j], acc[j][2], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[j][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[3], ax[j], acc[j][3], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -813,37 +815,35 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma64_kernel(GemmP p, int n_n
     };
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      // one MFMA, then at most one fragment read or one load (see the 32-k kernel); order held by sched_barrier
+      if (j < 2) bx[2 * j] = frag_b(bbuf, 2 * j, 2 * H);
+      else ax[2 * j - 4] = frag_a(abuf, 2 * j - 4, 2 * H);
+      if (!kFirst) acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[0], ay[j], acc[j][0], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (j < 2) bx[2 * j + 1] = frag_b(bbuf, 2 * j + 1, 2 * H);
+      else ax[2 * j - 3] = frag_a(abuf, 2 * j - 3, 2 * H);
+      if (!kFirst) acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[1], ay[j], acc[j][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       issue(j);
-      if (j < 2) {
-        bx[2 * j] = frag_b(bbuf, 2 * j, 2 * H);
-        bx[2 * j + 1] = frag_b(bbuf, 2 * j + 1, 2 * H);
-      } else {
-        ax[2 * j - 4] = frag_a(abuf, 2 * j - 4, 2 * H);
-        ax[2 * j - 3] = frag_a(abuf, 2 * j - 3, 2 * H);
-      }
-      if (!kFirst) {
-#pragma unroll
-        for (int fn = 0; fn < 4; ++fn)
-          acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[fn], ay[j], acc[j][fn], 0, 0, 0);
-      }
-      // keep the region as written (the reads of the next fragments go out a half-step's worth of
-      // MFMAs before their use); left alone, the scheduler sinks them down to the use and the
-      // matrix pipe waits out the LDS latency twice per half-step
+      if (!kFirst) acc[j][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[2], ay[j], acc[j][2], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!kFirst) acc[j][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(by[3], ay[j], acc[j][3], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      if (j < 2) by[2 * j] = frag_b(bbuf, 2 * j, 2 * H + 1);
+      else ay[2 * j - 4] = frag_a(abuf, 2 * j - 4, 2 * H + 1);
+      acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[0], ax[j], acc[j][0], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (j < 2) by[2 * j + 1] = frag_b(bbuf, 2 * j + 1, 2 * H + 1);
+      else ay[2 * j - 3] = frag_a(abuf, 2 * j - 3, 2 * H + 1);
+      acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[1], ax[j], acc[j][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       issue(4 + j);
-      if (j < 2) {
-        by[2 * j] = frag_b(bbuf, 2 * j, 2 * H + 1);
-        by[2 * j + 1] = frag_b(bbuf, 2 * j + 1, 2 * H + 1);
-      } else {
-        ay[2 * j - 4] = frag_a(abuf, 2 * j - 4, 2 * H + 1);
-        ay[2 * j - 3] = frag_a(abuf, 2 * j - 3, 2 * H + 1);
-      }
-#pragma unroll
-      for (int fn = 0; fn < 4; ++fn)
-        acc[j][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[fn], ax[j], acc[j][fn], 0, 0, 0);
+      acc[j][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[2], ax[j], acc[j][2], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[j][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx[3], ax[j], acc[j][3], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
