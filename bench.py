@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--workload", default="mixtral", choices=["tiny", "gpt2", "mixtral", "finegrained", "switch"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--chunks", type=int, default=0,
+                    help="also time the layer run in this many chunks (moe_layer_fwd_chunked / moe_layer_bwd_chunked, "
+                         "dispatch of the next chunk on a second stream); reported beside the headline figure")
     ap.add_argument("--calibrate-gemm", action="store_true",
                     help="also time the vendor library's plain bf16 GEMM (torch.matmul) for about a second per layout on this box: "
                          "context for the MFMA roofline fraction, since the sustained clock differs from box to box")
@@ -189,6 +192,25 @@ def main():
            "expert_gemm_tflops": round(achieved, 1), "roofline": roofline}
     if library_gemm is not None:
         out["library_gemm_reference"] = library_gemm
+    if args.chunks > 1:
+        aux = torch.cuda.Stream()
+
+        def step_chunked():
+            moe.moe_layer_fwd_chunked(cfg, d["x"], d["w_gate"], d["b_gate"], d["w1"], d["w3"], d["w2"], b.y, b.saved, b.ws,
+                                      args.chunks, aux)
+            moe.moe_layer_bwd_chunked(cfg, d["dy"], d["x"], d["w_gate"], d["w1"], d["w3"], d["w2"], b.saved, b.dx,
+                                      b.dw_gate, b.db_gate if has_bias else None, b.dw1, b.dw3, b.dw2, b.ws, args.chunks)
+
+        for _ in range(args.warmup):
+            step_chunked()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_chunked()
+        torch.cuda.synchronize()
+        ms_c = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["chunked"] = {"n_chunks": args.chunks, "streams": 2, "ms_per_step": round(ms_c, 3),
+                          "tokens_per_s": round(w.N / ms_c * 1e3, 1)}
 
     if not args.no_breakdown:
         bpe = 2 if w.dtype == S.DT_BF16 else 4

@@ -153,6 +153,32 @@ moe_status_t moe_layer_bwd(const moe_config_t* cfg, const void* dy, const void* 
                            void* dx, void* dw_gate, float* db_gate, void* dw1, void* dw3, void* dw2,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* The layer in chunks (Sec. 4.2, Fig. 5: the capacity dimension of the dispatched tensor is cut into r
+ * parts that move through dispatch -> experts one after the other so that the steps of neighbouring
+ * parts can overlap).  Chunk c of n_chunks holds rows floor(c n / r) .. floor((c+1) n / r) - 1 of the
+ * n rows of every expert.  The gate runs once over all tokens, the I-ordering once at the end.
+ * Every output and every byte of `saved` is identical to moe_layer_fwd: rows are independent in the
+ * ordering function and in the expert FFN, and no contraction is split.
+ * n_chunks: 1 .. MOE_MAX_CHUNKS (1 = moe_layer_fwd).  aux_stream: NULL, or a second hipStream_t on which
+ * the dispatch of chunk c+1 is enqueued while chunk c is in the expert FFN on `stream`; on return all work
+ * of aux_stream is ordered before what the caller enqueues next on `stream` (the library records and
+ * waits on events of its own; it creates them once, on first use).  Calls that overlap on one device
+ * must not share aux_stream.  Other arguments and errors as moe_layer_fwd. */
+#define MOE_MAX_CHUNKS 16
+moe_status_t moe_layer_fwd_chunked(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
+                                   const void* w1, const void* w3, const void* w2, void* y, void* saved,
+                                   size_t saved_bytes, void* workspace, size_t workspace_bytes, int32_t n_chunks,
+                                   void* stream, void* aux_stream);
+
+/* Backward of the layer in chunks: the row-wise products (dq.W2^T with the activation derivative, and
+ * da.W1^T) run chunk by chunk; the weight gradients contract over the rows of an expert and are computed
+ * whole, after the last chunk, so that every output is identical to moe_layer_bwd.  Single stream.
+ * `saved` may come from moe_layer_fwd or moe_layer_fwd_chunked with any n_chunks. */
+moe_status_t moe_layer_bwd_chunked(const moe_config_t* cfg, const void* dy, const void* x, const void* w_gate,
+                                   const void* w1, const void* w3, const void* w2, const void* saved, size_t saved_bytes,
+                                   void* dx, void* dw_gate, float* db_gate, void* dw1, void* dw3, void* dw2,
+                                   void* workspace, size_t workspace_bytes, int32_t n_chunks, void* stream);
+
 /* Where inside `saved` a tensor lives (for inspection and tests).  Host function. */
 typedef enum {
   MOE_SAVED_LOGITS = 0, MOE_SAVED_PROBS, MOE_SAVED_TOPK_IDX, MOE_SAVED_TOPK_W, MOE_SAVED_POS, MOE_SAVED_ROW_OF,

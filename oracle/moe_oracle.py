@@ -359,6 +359,50 @@ def layer_bwd(dy, x, w_gate, b_gate, w1, w3, w2, fwd, act, renormalize, add_resi
                 dq=dq, dtopk_w=dtopk_w, dxe=dxe, dlogits=dl)
 
 
+# ----------------------------------------------------------------------------- the layer in r chunks (Sec. 4.2)
+# Sec. 4.2 / Fig. 5 cut the capacity dimension of the dispatched tensor into r parts that go through
+# dispatch -> experts one after the other.  Rows are independent there, so the result is that of r = 1.
+
+def chunk_bounds(offsets, r):
+    """begin[c,e], end[c,e]: chunk c of r holds rows floor(c n / r) .. floor((c+1) n / r) - 1 of the n rows of expert e."""
+    e_cnt = len(offsets) - 1
+    begin = np.zeros((r, e_cnt), np.int64)
+    end = np.zeros((r, e_cnt), np.int64)
+    for e in range(e_cnt):
+        lo, n = int(offsets[e]), int(offsets[e + 1]) - int(offsets[e])
+        for c in range(r):
+            begin[c, e] = lo + (c * n) // r
+            end[c, e] = lo + ((c + 1) * n) // r
+    return begin, end
+
+
+def layer_fwd_chunked(x, w_gate, b_gate, w1, w3, w2, k, cap, act, renormalize, add_residual, r,
+                      logit_dtype=np.float32):
+    """layer_fwd with ordering and experts done chunk by chunk, in chunk order."""
+    out = route(x, w_gate, b_gate, k, cap, renormalize, logit_dtype)
+    n_rows = int(out["offsets"][-1])
+    h = w1.shape[2]
+    xe = np.zeros((n_rows, x.shape[1]))
+    q = np.zeros((n_rows, x.shape[1]))
+    a1 = np.zeros((n_rows, h))
+    a3 = np.zeros((n_rows, h)) if act == ACT_SWIGLU else None
+    hh = np.zeros((n_rows, h))
+    begin, end = chunk_bounds(out["offsets"], r)
+    for c in range(r):
+        for e in range(len(out["offsets"]) - 1):
+            lo, hi = int(begin[c, e]), int(end[c, e])
+            if hi == lo:
+                continue
+            xe[lo:hi] = x[out["src_of_row"][lo:hi] // k]  # ordering function, these rows only
+            qe, a1e, a3e, hhe = expert_rows_fwd(xe[lo:hi], w1[e], w3[e] if a3 is not None else None, w2[e], act)
+            q[lo:hi], a1[lo:hi], hh[lo:hi] = qe, a1e, hhe
+            if a3 is not None:
+                a3[lo:hi] = a3e
+    y = inverse_order(q, out["topk_w"], out["row_of"], x if add_residual else None)
+    out.update(xe=xe, q=q, saved=(a1, a3, hh), y=y)
+    return out
+
+
 # ----------------------------------------------------------------------------- sampled evaluation for large shapes
 # Given the (cheap, full) routing, rows are independent: outputs for a subset of tokens, and columns of
 # the weight gradients for a subset of hidden units, follow from the same per-row definitions above.

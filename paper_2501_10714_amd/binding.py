@@ -20,7 +20,9 @@ _LIB = None
 
 ENTRY_POINTS = ["moe_capacity", "moe_workspace_bytes", "moe_route", "moe_dispatch", "moe_dispatch_bwd",
                 "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_combine", "moe_combine_bwd", "moe_route_bwd",
-                "moe_layer_fwd", "moe_layer_bwd", "moe_saved_offset", "moe_last_error"]
+                "moe_layer_fwd", "moe_layer_bwd", "moe_layer_fwd_chunked", "moe_layer_bwd_chunked", "moe_saved_offset",
+                "moe_last_error"]
+MAX_CHUNKS = 16  # MOE_MAX_CHUNKS
 
 
 class MoeError(RuntimeError):
@@ -153,3 +155,16 @@ def moe_layer_bwd(cfg, dy, x, w_gate, w1, w3, w2, saved, dx, dw_gate, db_gate, d
     _check(load().moe_layer_bwd(C.byref(cfg), _p(dy), _p(x), _p(w_gate), _p(w1), _p(w3), _p(w2), _p(saved), _sz(saved),
                                 _p(dx), _p(dw_gate), _p(db_gate), _p(dw1), _p(dw3), _p(dw2), _p(ws), _sz(ws),
                                 _stream()))
+
+
+def moe_layer_fwd_chunked(cfg, x, w_gate, b_gate, w1, w3, w2, y, saved, ws, n_chunks, aux_stream=None):
+    """aux_stream: a torch.cuda.Stream (or None) for the dispatch of the next chunk."""
+    aux = C.c_void_p(None if aux_stream is None else aux_stream.cuda_stream)
+    _check(load().moe_layer_fwd_chunked(C.byref(cfg), _p(x), _p(w_gate), _p(b_gate), _p(w1), _p(w3), _p(w2), _p(y),
+                                        _p(saved), _sz(saved), _p(ws), _sz(ws), C.c_int32(n_chunks), _stream(), aux))
+
+
+def moe_layer_bwd_chunked(cfg, dy, x, w_gate, w1, w3, w2, saved, dx, dw_gate, db_gate, dw1, dw3, dw2, ws, n_chunks):
+    _check(load().moe_layer_bwd_chunked(C.byref(cfg), _p(dy), _p(x), _p(w_gate), _p(w1), _p(w3), _p(w2), _p(saved),
+                                        _sz(saved), _p(dx), _p(dw_gate), _p(db_gate), _p(dw1), _p(dw3), _p(dw2), _p(ws),
+                                        _sz(ws), C.c_int32(n_chunks), _stream()))

@@ -95,10 +95,25 @@ BwdPlan bwd_plan(const moe_config_t& c) {
   return p;
 }
 
-size_t workspace_bytes(const moe_config_t& c) {
+// The workspace ends in the row ranges of the chunked layer: begin[r][E], end[r][E], r <= MOE_MAX_CHUNKS.
+size_t chunk_bounds_offset(const moe_config_t& c) {
   size_t w = route_workspace_bytes(c);
   size_t b = bwd_plan(c).bytes;
-  return w > b ? w : b;
+  return align_up(w > b ? w : b, 256);
+}
+size_t workspace_bytes(const moe_config_t& c) {
+  return chunk_bounds_offset(c) + align_up((size_t)2 * MOE_MAX_CHUNKS * c.n_experts * sizeof(int32_t), 256);
+}
+
+// Events that order the two streams of the chunked forward pass; created on first use, never destroyed.
+hipEvent_t* chunk_events() {
+  static hipEvent_t ev[MOE_MAX_CHUNKS + 1];
+  static bool ok = [] {
+    for (auto& e : ev)
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return false;
+    return true;
+  }();
+  return ok ? ev : nullptr;
 }
 
 inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
@@ -177,7 +192,7 @@ moe_status_t moe_expert_ffn_fwd(const moe_config_t* cfg, const void* xe, const i
   NOT_NULL(xe); NOT_NULL(offsets); NOT_NULL(w1); NOT_NULL(w2); NOT_NULL(q); NOT_NULL(a1); NOT_NULL(hh);
   if (cfg->act == MOE_ACT_SWIGLU) { NOT_NULL(w3); NOT_NULL(a3); }
   (void)workspace; (void)workspace_bytes_;
-  return launch_expert_fwd(*cfg, xe, offsets, w1, w3, w2, q, a1, a3, hh, as_stream(stream));
+  return launch_expert_fwd(*cfg, xe, offsets, nullptr, w1, w3, w2, q, a1, a3, hh, as_stream(stream));
 }
 
 moe_status_t moe_expert_ffn_bwd(const moe_config_t* cfg, const void* dq, const void* xe, const int32_t* offsets,
@@ -219,46 +234,95 @@ moe_status_t moe_route_bwd(const moe_config_t* cfg, const void* x, const void* w
                           as_stream(stream));
 }
 
-moe_status_t moe_layer_fwd(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
-                           const void* w1, const void* w3, const void* w2, void* y, void* saved, size_t saved_bytes,
-                           void* workspace, size_t workspace_bytes_, void* stream) {
+static moe_status_t layer_fwd_impl(const char* fn, const moe_config_t* cfg, const void* x, const void* w_gate,
+                                   const float* b_gate, const void* w1, const void* w3, const void* w2, void* y,
+                                   void* saved, size_t saved_bytes, void* workspace, size_t workspace_bytes_, int r,
+                                   void* stream, void* aux_stream) {
   CHECK_CFG(cfg);
   NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(w1); NOT_NULL(w2); NOT_NULL(y); NOT_NULL(saved);
   if (cfg->act == MOE_ACT_SWIGLU) NOT_NULL(w3);
+  REQUIRE(r >= 1 && r <= MOE_MAX_CHUNKS, MOE_ERR_INVALID_ARG, "%s: %d chunks, must be 1..%d", fn, r, MOE_MAX_CHUNKS);
   CHECK_WS(cfg, workspace, workspace_bytes_);
   SavedPlan sp = saved_plan(*cfg);
-  REQUIRE(saved_bytes >= sp.bytes, MOE_ERR_WORKSPACE, "moe_layer_fwd: saved blob of %zu bytes, need %zu", saved_bytes,
-          sp.bytes);
+  REQUIRE(saved_bytes >= sp.bytes, MOE_ERR_WORKSPACE, "%s: saved blob of %zu bytes, need %zu", fn, saved_bytes, sp.bytes);
   unsigned char* sv = static_cast<unsigned char*>(saved);
   auto at = [&](int w) { return static_cast<void*>(sv + sp.off[w]); };
   hipStream_t s = as_stream(stream);
+  void* a3 = cfg->act == MOE_ACT_SWIGLU ? at(MOE_SAVED_A3) : nullptr;
+  const int32_t* offsets = (const int32_t*)at(MOE_SAVED_OFFSETS);
   moe_status_t st = launch_route(*cfg, x, w_gate, b_gate, (float*)at(MOE_SAVED_LOGITS), (float*)at(MOE_SAVED_PROBS),
                                  (int32_t*)at(MOE_SAVED_TOPK_IDX), (float*)at(MOE_SAVED_TOPK_W),
                                  (int32_t*)at(MOE_SAVED_POS), (int32_t*)at(MOE_SAVED_ROW_OF),
                                  (int32_t*)at(MOE_SAVED_COUNT), (int32_t*)at(MOE_SAVED_OFFSETS),
                                  (int32_t*)at(MOE_SAVED_SRC_OF_ROW), workspace, s);
   if (st != MOE_OK) return st;
-  st = launch_dispatch(*cfg, x, (const int32_t*)at(MOE_SAVED_ROW_OF), at(MOE_SAVED_XE), s);
-  if (st != MOE_OK) return st;
-  st = launch_expert_fwd(*cfg, at(MOE_SAVED_XE), (const int32_t*)at(MOE_SAVED_OFFSETS), w1, w3, w2, at(MOE_SAVED_Q),
-                         at(MOE_SAVED_A1), cfg->act == MOE_ACT_SWIGLU ? at(MOE_SAVED_A3) : nullptr, at(MOE_SAVED_HH), s);
-  if (st != MOE_OK) return st;
+  if (r == 1) {
+    st = launch_dispatch(*cfg, x, (const int32_t*)at(MOE_SAVED_ROW_OF), at(MOE_SAVED_XE), s);
+    if (st != MOE_OK) return st;
+    st = launch_expert_fwd(*cfg, at(MOE_SAVED_XE), offsets, nullptr, w1, w3, w2, at(MOE_SAVED_Q), at(MOE_SAVED_A1), a3,
+                           at(MOE_SAVED_HH), s);
+    if (st != MOE_OK) return st;
+  } else {
+    // FSMoE Sec. 4.2 on one GPU: the rows of every expert are cut into r chunks; chunk c is dispatched (on the
+    // auxiliary stream when there is one) while chunk c - 1 is in the expert FFN.  Rows are independent in
+    // dispatch and in the FFN, so every byte of xe, a1, a3, hh, q is what r = 1 writes.
+    int32_t* begin = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace) + chunk_bounds_offset(*cfg));
+    int32_t* end = begin + (size_t)MOE_MAX_CHUNKS * cfg->n_experts;
+    st = launch_chunk_bounds(*cfg, offsets, r, begin, end, s);
+    if (st != MOE_OK) return st;
+    hipStream_t aux = as_stream(aux_stream);
+    hipEvent_t* ev = nullptr;
+    if (aux_stream != nullptr && aux != s) {
+      ev = chunk_events();
+      REQUIRE(ev != nullptr, MOE_ERR_DEVICE, "%s: could not create events", fn);
+      REQUIRE(hipEventRecord(ev[MOE_MAX_CHUNKS], s) == hipSuccess && hipStreamWaitEvent(aux, ev[MOE_MAX_CHUNKS], 0) == hipSuccess,
+              MOE_ERR_DEVICE, "%s: stream ordering failed", fn);
+    }
+    for (int c = 0; c < r; ++c) {
+      const int32_t* bc = begin + (size_t)c * cfg->n_experts;
+      const int32_t* ec = end + (size_t)c * cfg->n_experts;
+      st = launch_dispatch_rows(*cfg, x, (const int32_t*)at(MOE_SAVED_SRC_OF_ROW), bc, ec, r, at(MOE_SAVED_XE),
+                                ev != nullptr ? aux : s);
+      if (st != MOE_OK) return st;
+      if (ev != nullptr)
+        REQUIRE(hipEventRecord(ev[c], aux) == hipSuccess && hipStreamWaitEvent(s, ev[c], 0) == hipSuccess, MOE_ERR_DEVICE,
+                "%s: stream ordering failed", fn);
+      st = launch_expert_fwd(*cfg, at(MOE_SAVED_XE), bc, ec, w1, w3, w2, at(MOE_SAVED_Q), at(MOE_SAVED_A1), a3,
+                             at(MOE_SAVED_HH), s);
+      if (st != MOE_OK) return st;
+    }
+  }
   return launch_combine(*cfg, at(MOE_SAVED_Q), (const float*)at(MOE_SAVED_TOPK_W), (const int32_t*)at(MOE_SAVED_ROW_OF),
                         x, y, s);
 }
 
-moe_status_t moe_layer_bwd(const moe_config_t* cfg, const void* dy, const void* x, const void* w_gate, const void* w1,
-                           const void* w3, const void* w2, const void* saved, size_t saved_bytes, void* dx,
-                           void* dw_gate, float* db_gate, void* dw1, void* dw3, void* dw2, void* workspace,
-                           size_t workspace_bytes_, void* stream) {
+moe_status_t moe_layer_fwd(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
+                           const void* w1, const void* w3, const void* w2, void* y, void* saved, size_t saved_bytes,
+                           void* workspace, size_t workspace_bytes_, void* stream) {
+  return layer_fwd_impl("moe_layer_fwd", cfg, x, w_gate, b_gate, w1, w3, w2, y, saved, saved_bytes, workspace,
+                        workspace_bytes_, 1, stream, nullptr);
+}
+
+moe_status_t moe_layer_fwd_chunked(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
+                                   const void* w1, const void* w3, const void* w2, void* y, void* saved,
+                                   size_t saved_bytes, void* workspace, size_t workspace_bytes_, int32_t n_chunks,
+                                   void* stream, void* aux_stream) {
+  return layer_fwd_impl("moe_layer_fwd_chunked", cfg, x, w_gate, b_gate, w1, w3, w2, y, saved, saved_bytes, workspace,
+                        workspace_bytes_, n_chunks, stream, aux_stream);
+}
+
+static moe_status_t layer_bwd_impl(const char* fn, const moe_config_t* cfg, const void* dy, const void* x,
+                                   const void* w_gate, const void* w1, const void* w3, const void* w2, const void* saved,
+                                   size_t saved_bytes, void* dx, void* dw_gate, float* db_gate, void* dw1, void* dw3,
+                                   void* dw2, void* workspace, size_t workspace_bytes_, int r, void* stream) {
   CHECK_CFG(cfg);
   NOT_NULL(dy); NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(w1); NOT_NULL(w2); NOT_NULL(saved); NOT_NULL(dx);
   NOT_NULL(dw_gate); NOT_NULL(dw1); NOT_NULL(dw2);
   if (cfg->act == MOE_ACT_SWIGLU) { NOT_NULL(w3); NOT_NULL(dw3); }
+  REQUIRE(r >= 1 && r <= MOE_MAX_CHUNKS, MOE_ERR_INVALID_ARG, "%s: %d chunks, must be 1..%d", fn, r, MOE_MAX_CHUNKS);
   CHECK_WS(cfg, workspace, workspace_bytes_);
   SavedPlan sp = saved_plan(*cfg);
-  REQUIRE(saved_bytes >= sp.bytes, MOE_ERR_WORKSPACE, "moe_layer_bwd: saved blob of %zu bytes, need %zu", saved_bytes,
-          sp.bytes);
+  REQUIRE(saved_bytes >= sp.bytes, MOE_ERR_WORKSPACE, "%s: saved blob of %zu bytes, need %zu", fn, saved_bytes, sp.bytes);
   const unsigned char* sv = static_cast<const unsigned char*>(saved);
   auto at = [&](int w) { return static_cast<const void*>(sv + sp.off[w]); };
   BwdPlan bp = bwd_plan(*cfg);
@@ -268,16 +332,50 @@ moe_status_t moe_layer_bwd(const moe_config_t* cfg, const void* dy, const void* 
   float* dtw = reinterpret_cast<float*>(w + bp.off_dtw);
   hipStream_t s = as_stream(stream);
   const int32_t* row_of = (const int32_t*)at(MOE_SAVED_ROW_OF);
+  const int32_t* offsets = (const int32_t*)at(MOE_SAVED_OFFSETS);
+  const void* a3 = cfg->act == MOE_ACT_SWIGLU ? at(MOE_SAVED_A3) : nullptr;
   moe_status_t st = launch_combine_bwd(*cfg, dy, at(MOE_SAVED_Q), (const float*)at(MOE_SAVED_TOPK_W), row_of, dq, dtw, s);
   if (st != MOE_OK) return st;
-  st = launch_expert_bwd(*cfg, dq, at(MOE_SAVED_XE), (const int32_t*)at(MOE_SAVED_OFFSETS), w1, w3, w2, at(MOE_SAVED_A1),
-                         cfg->act == MOE_ACT_SWIGLU ? at(MOE_SAVED_A3) : nullptr, at(MOE_SAVED_HH), dxe, dw1, dw3, dw2,
-                         w + bp.off_expert, s);
-  if (st != MOE_OK) return st;
+  if (r == 1) {
+    st = launch_expert_bwd(*cfg, dq, at(MOE_SAVED_XE), offsets, w1, w3, w2, at(MOE_SAVED_A1), a3, at(MOE_SAVED_HH), dxe,
+                           dw1, dw3, dw2, w + bp.off_expert, s);
+    if (st != MOE_OK) return st;
+  } else {
+    // the row-wise products (dhh with the activation derivative, dxe) chunk by chunk; the weight gradients
+    // contract over the rows of an expert and stay whole, so that their rounding is that of r = 1
+    int32_t* begin = reinterpret_cast<int32_t*>(w + chunk_bounds_offset(*cfg));
+    int32_t* end = begin + (size_t)MOE_MAX_CHUNKS * cfg->n_experts;
+    st = launch_chunk_bounds(*cfg, offsets, r, begin, end, s);
+    if (st != MOE_OK) return st;
+    for (int c = 0; c < r; ++c) {
+      st = launch_expert_bwd_dgrad(*cfg, dq, begin + (size_t)c * cfg->n_experts, end + (size_t)c * cfg->n_experts, w1, w3,
+                                   w2, at(MOE_SAVED_A1), a3, dxe, w + bp.off_expert, 3, s);
+      if (st != MOE_OK) return st;
+    }
+    st = launch_expert_bwd_wgrad(*cfg, dq, at(MOE_SAVED_XE), offsets, at(MOE_SAVED_HH), dw1, dw3, dw2, w + bp.off_expert,
+                                 3, s);
+    if (st != MOE_OK) return st;
+  }
   st = launch_dispatch_bwd(*cfg, dxe, row_of, dy, dx, s);
   if (st != MOE_OK) return st;
   return launch_route_bwd(*cfg, x, w_gate, (const float*)at(MOE_SAVED_PROBS), (const int32_t*)at(MOE_SAVED_TOPK_IDX),
                           (const int32_t*)at(MOE_SAVED_POS), dtw, dw_gate, db_gate, dx, w + bp.off_route, s);
+}
+
+moe_status_t moe_layer_bwd(const moe_config_t* cfg, const void* dy, const void* x, const void* w_gate, const void* w1,
+                           const void* w3, const void* w2, const void* saved, size_t saved_bytes, void* dx,
+                           void* dw_gate, float* db_gate, void* dw1, void* dw3, void* dw2, void* workspace,
+                           size_t workspace_bytes_, void* stream) {
+  return layer_bwd_impl("moe_layer_bwd", cfg, dy, x, w_gate, w1, w3, w2, saved, saved_bytes, dx, dw_gate, db_gate, dw1,
+                        dw3, dw2, workspace, workspace_bytes_, 1, stream);
+}
+
+moe_status_t moe_layer_bwd_chunked(const moe_config_t* cfg, const void* dy, const void* x, const void* w_gate,
+                                   const void* w1, const void* w3, const void* w2, const void* saved, size_t saved_bytes,
+                                   void* dx, void* dw_gate, float* db_gate, void* dw1, void* dw3, void* dw2,
+                                   void* workspace, size_t workspace_bytes_, int32_t n_chunks, void* stream) {
+  return layer_bwd_impl("moe_layer_bwd_chunked", cfg, dy, x, w_gate, w1, w3, w2, saved, saved_bytes, dx, dw_gate, db_gate,
+                        dw1, dw3, dw2, workspace, workspace_bytes_, n_chunks, stream);
 }
 
 const char* moe_last_error(void) { return moe::g_err; }

@@ -117,6 +117,11 @@ moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* 
                               float* db_gate, void* dx, void* ws, hipStream_t s);
 // order.hip
 moe_status_t launch_dispatch(const moe_config_t& c, const void* x, const int32_t* row_of, void* xe, hipStream_t s);
+// chunked layer (FSMoE Sec. 4.2): row ranges of chunk c of every expert, and the dispatch of one chunk
+moe_status_t launch_chunk_bounds(const moe_config_t& c, const int32_t* offsets, int r, int32_t* begin, int32_t* end,
+                                 hipStream_t s);
+moe_status_t launch_dispatch_rows(const moe_config_t& c, const void* x, const int32_t* src_of_row, const int32_t* begin,
+                                  const int32_t* end, int r, void* xe, hipStream_t s);
 moe_status_t launch_dispatch_bwd(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* dy, void* dx,
                                  hipStream_t s);
 moe_status_t launch_combine(const moe_config_t& c, const void* q, const float* topk_w, const int32_t* row_of,
@@ -125,8 +130,18 @@ moe_status_t launch_combine_bwd(const moe_config_t& c, const void* dy, const voi
                                 const int32_t* row_of, void* dq, float* dtopk_w, hipStream_t s);
 // expert_ffn.hip
 size_t expert_bwd_workspace_bytes(const moe_config_t& c);
-moe_status_t launch_expert_fwd(const moe_config_t& c, const void* xe, const int32_t* offsets, const void* w1,
-                               const void* w3, const void* w2, void* q, void* a1, void* a3, void* hh, hipStream_t s);
+// row_end == NULL: whole experts; else rows [offsets[e], row_end[e]) of every expert (one chunk)
+moe_status_t launch_expert_fwd(const moe_config_t& c, const void* xe, const int32_t* offsets, const int32_t* row_end,
+                               const void* w1, const void* w3, const void* w2, void* q, void* a1, void* a3, void* hh,
+                               hipStream_t s);
+// which: bit 0 = dhh (-> da1, da3 in ws), bit 1 = dxe
+moe_status_t launch_expert_bwd_dgrad(const moe_config_t& c, const void* dq, const int32_t* offsets,
+                                     const int32_t* row_end, const void* w1, const void* w3, const void* w2,
+                                     const void* a1, const void* a3, void* dxe, void* ws, int which, hipStream_t s);
+// which: bit 0 = dW2, bit 1 = dW1 (, dW3); needs da1 (, da3) in ws
+moe_status_t launch_expert_bwd_wgrad(const moe_config_t& c, const void* dq, const void* xe, const int32_t* offsets,
+                                     const void* hh, void* dw1, void* dw3, void* dw2, void* ws, int which,
+                                     hipStream_t s);
 moe_status_t launch_expert_bwd(const moe_config_t& c, const void* dq, const void* xe, const int32_t* offsets,
                                const void* w1, const void* w3, const void* w2, const void* a1, const void* a3,
                                const void* hh, void* dxe, void* dw1, void* dw3, void* dw2, void* ws, hipStream_t s);

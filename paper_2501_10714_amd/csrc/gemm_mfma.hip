@@ -192,7 +192,7 @@ template <bool RAGGED_K>
 __device__ __forceinline__ int count_tiles(const GemmP& p, int n_nt, int mt_fix) {
   if (RAGGED_K) return ((p.n_pairs == 2) ? 2 * p.n_experts : p.n_experts) * mt_fix * n_nt;
   int total = 0;
-  for (int e = 0; e < p.n_experts; ++e) total += ((p.offsets[e + 1] - p.offsets[e] + BM - 1) / BM) * n_nt;
+  for (int e = 0; e < p.n_experts; ++e) total += ((p.row_end[e] - p.offsets[e] + BM - 1) / BM) * n_nt;
   return total;
 }
 // Logical tile index L < count_tiles() -> (expert, row tile, column tile): per expert, bands of kBand
@@ -206,7 +206,7 @@ __device__ __forceinline__ TileId tile_at(const GemmP& p, int n_nt, int mt_fix, 
     L -= g * mt_fix * n_nt;
   } else {
     for (;; ++g) {
-      mt_g = (p.offsets[g + 1] - p.offsets[g] + BM - 1) / BM;
+      mt_g = (p.row_end[g] - p.offsets[g] + BM - 1) / BM;
       const int cnt = mt_g * n_nt;
       if (L < cnt) break;
       L -= cnt;
@@ -220,7 +220,7 @@ __device__ __forceinline__ TileId tile_at(const GemmP& p, int n_nt, int mt_fix, 
   t.e = g % p.n_experts;
   t.set = g / p.n_experts;
   t.r0 = p.offsets[t.e];
-  t.rows = p.offsets[t.e + 1] - t.r0;
+  t.rows = p.row_end[t.e] - t.r0;
   t.valid = true;
   return t;
 }

@@ -28,7 +28,9 @@ struct GemmP {
   const void* B[2];
   void* C[3];
   const void* X[2];        // saved activations read by the backward epilogues, same layout as C
-  const int32_t* offsets;  // [E+1] device
+  const int32_t* offsets;  // device: first row of every group ([E]; offsets[E] is only read through row_end)
+  const int32_t* row_end;  // device: one past the last row of every group (offsets + 1 for whole experts; a
+                           // chunk of the rows of every expert when the layer is run in chunks, FSMoE Sec. 4.2)
   long sAi, sAk;           // element strides of A(i,k)
   long sBk, sBn;           // element strides of B(k,n)
   long gB, gC;             // per-expert strides (elements) of weights / weight gradients

@@ -18,7 +18,7 @@ __global__ __launch_bounds__(256) void gg_plain_kernel(GemmP p) {
   const int g = blockIdx.z;
   const int e = g % p.n_experts;
   const int set = g / p.n_experts;  // only > 0 for ragged-K launches with two outputs
-  const int r0 = p.offsets[e], r1 = p.offsets[e + 1];
+  const int r0 = p.offsets[e], r1 = p.row_end[e];
   const int rows = r1 - r0;
   const int Mg = RAGGED_K ? p.Mfix : rows;
   const int Kg = RAGGED_K ? rows : p.Kfix;

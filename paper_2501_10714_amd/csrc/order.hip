@@ -46,6 +46,37 @@ __global__ __launch_bounds__(kBlock) void dispatch_kernel(const T* __restrict__ 
   }
 }
 
+// One chunk of the ordering function, expert rows [begin[e], end[e]) of every expert e (blockIdx.y):
+// xe[row, :] = x[src_of_row[row] / top_k, :].  Walks expert rows, so x is read once per kept assignment.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void dispatch_rows_kernel(const T* __restrict__ x, const int32_t* __restrict__ src_of_row,
+                                                               const int32_t* __restrict__ begin,
+                                                               const int32_t* __restrict__ end, T* __restrict__ xe,
+                                                               int d_model, int top_k, int tpr) {
+  constexpr int V = Elem<T>::kVec;
+  const int rpb = kBlock / tpr;
+  const int row = begin[blockIdx.y] + blockIdx.x * rpb + threadIdx.x / tpr;
+  if (row >= end[blockIdx.y]) return;
+  const int lane = threadIdx.x % tpr;
+  const int chunks = d_model / V;
+  const int t = src_of_row[row] / top_k;
+  const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)t * d_model);
+  uint4* dst = reinterpret_cast<uint4*>(xe + (size_t)row * d_model);
+  for (int c = lane; c < chunks; c += tpr) dst[c] = src[c];
+}
+
+// Chunk c of r of expert e holds its rows floor(c n / r) .. floor((c + 1) n / r) - 1, n = rows of the expert
+// (FSMoE Sec. 4.2: the capacity dimension is cut into r parts).  begin, end: [r][E].
+__global__ void chunk_bounds_kernel(const int32_t* __restrict__ offsets, int n_experts, int r,
+                                    int32_t* __restrict__ begin, int32_t* __restrict__ end) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= r * n_experts) return;
+  const int c = i / n_experts, e = i % n_experts;
+  const long n = offsets[e + 1] - offsets[e];
+  begin[i] = offsets[e] + (int)(c * n / r);
+  end[i] = offsets[e] + (int)((c + 1) * n / r);
+}
+
 // out[t,:] = sum_j scale_j * src[row_of[t,j], :] (+ res[t,:]);  scale_j = w[t,j] or 1
 template <typename T, bool kWeighted>
 __global__ __launch_bounds__(kBlock) void gather_sum_kernel(const T* __restrict__ src, const float* __restrict__ w,
@@ -194,6 +225,33 @@ moe_status_t combine_bwd_t(const moe_config_t& c, const void* dy, const void* q,
 
 moe_status_t launch_dispatch(const moe_config_t& c, const void* x, const int32_t* row_of, void* xe, hipStream_t s) {
   return c.dtype == MOE_BF16 ? dispatch_t<bf16_t>(c, x, row_of, xe, s) : dispatch_t<float>(c, x, row_of, xe, s);
+}
+
+moe_status_t launch_chunk_bounds(const moe_config_t& c, const int32_t* offsets, int r, int32_t* begin, int32_t* end,
+                                 hipStream_t s) {
+  const int n = r * c.n_experts;
+  hipLaunchKernelGGL(chunk_bounds_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, s, offsets, c.n_experts, r, begin, end);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
+}
+
+moe_status_t launch_dispatch_rows(const moe_config_t& c, const void* x, const int32_t* src_of_row, const int32_t* begin,
+                                  const int32_t* end, int r, void* xe, hipStream_t s) {
+  const bool bf16 = c.dtype == MOE_BF16;
+  const RowMap m = row_map(c.d_model / (bf16 ? 8 : 4));
+  // an expert is chosen at most once per token and holds at most the capacity: a chunk has at most ceil(that / r) rows
+  long rows = c.n_tokens;
+  if (c.capacity > 0 && c.capacity < rows) rows = c.capacity;
+  const int per_chunk = (int)((rows + r - 1) / r);
+  const dim3 grid(ceil_div(per_chunk, m.rpb), c.n_experts);
+  if (bf16)
+    hipLaunchKernelGGL(dispatch_rows_kernel<bf16_t>, grid, dim3(kBlock), 0, s, static_cast<const bf16_t*>(x), src_of_row,
+                       begin, end, static_cast<bf16_t*>(xe), c.d_model, c.top_k, m.tpr);
+  else
+    hipLaunchKernelGGL(dispatch_rows_kernel<float>, grid, dim3(kBlock), 0, s, static_cast<const float*>(x), src_of_row,
+                       begin, end, static_cast<float*>(xe), c.d_model, c.top_k, m.tpr);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
 }
 
 moe_status_t launch_dispatch_bwd(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* dy, void* dx,

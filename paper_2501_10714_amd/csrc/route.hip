@@ -691,7 +691,7 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
   MOE_CHECK_LAUNCH();
   {  // dx += dlb.wgp^T : [N,ep] x [ep,M], B(k=e, n=m) = wgp[m][e]
     GemmP g = {};
-    g.offsets = tok + p.nsplit + 1; g.n_experts = 1; g.n_pairs = 1;
+    g.offsets = tok + p.nsplit + 1; g.row_end = g.offsets + 1; g.n_experts = 1; g.n_pairs = 1;
     g.A[0] = dlb; g.sAi = p.ep; g.sAk = 1;
     g.B[0] = wgp; g.sBk = 1; g.sBn = p.ep; g.gB = 0;
     g.C[0] = dx; g.ldc = c.d_model; g.N = c.d_model; g.Kfix = p.ep;
@@ -701,7 +701,7 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
   }
   {  // part[g] = x_g^T.dlb_g : [M,rows] x [rows,ep] for every 512-token group
     GemmP g = {};
-    g.offsets = tok; g.n_experts = p.nsplit; g.n_pairs = 1;
+    g.offsets = tok; g.row_end = g.offsets + 1; g.n_experts = p.nsplit; g.n_pairs = 1;
     g.A[0] = x; g.sAi = 1; g.sAk = c.d_model;
     g.B[0] = dlb; g.sBk = p.ep; g.sBn = 1;
     g.C[0] = part; g.ldc = p.ep; g.gC = (long)c.d_model * p.ep;

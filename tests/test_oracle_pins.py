@@ -418,3 +418,44 @@ def test_sampled_functions_match_full(act, renorm, resid, cap):
         assert np.allclose(c2, g["dw2"][ex][cols, :], rtol=1e-12, atol=1e-13)
         if w3 is not None:
             assert np.allclose(c3, g["dw3"][ex][:, cols], rtol=1e-12, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- the layer in chunks (Sec. 4.2)
+
+@pytest.mark.parametrize("r", [1, 2, 3, 5, 16])
+def test_chunk_bounds_partition_every_expert(r):
+    """Chunks of an expert are consecutive, disjoint, cover its rows, and differ in size by at most one row;
+    checked against a brute-force assignment of every row to the chunk c with c*n <= i*r < (c+1)*n... by counting."""
+    counts = np.array([0, 1, 2, 7, 16, 17, 255, 256, 1000])
+    offsets = np.concatenate([[0], np.cumsum(counts)])
+    begin, end = O.chunk_bounds(offsets, r)
+    for e, n in enumerate(counts):
+        assert begin[0, e] == offsets[e] and end[r - 1, e] == offsets[e + 1]
+        assert (end[:-1, e] == begin[1:, e]).all()
+        sizes = end[:, e] - begin[:, e]
+        assert sizes.sum() == n and sizes.max() - sizes.min() <= 1
+        # row i (0-based) of n lies in chunk c iff floor(c n / r) <= i < floor((c+1) n / r); brute force over rows
+        for c in range(r):
+            rows = [i for i in range(n) if (c * n) // r <= i < ((c + 1) * n) // r]
+            assert len(rows) == sizes[c]
+            if rows:
+                assert offsets[e] + rows[0] == begin[c, e] and offsets[e] + rows[-1] + 1 == end[c, e]
+
+
+@pytest.mark.parametrize("act,k,cap,r", [(O.ACT_SWIGLU, 2, 0, 3), (O.ACT_GELU_TANH, 1, 4, 2), (O.ACT_RELU, 3, 5, 16)])
+def test_chunked_layer_equals_whole_layer(act, k, cap, r):
+    """Sec. 4.2: cutting the capacity dimension into r chunks does not change what the layer computes."""
+    g = rng(200 + r)
+    n, m, h, e = 23, 6, 7, 4
+    x = g.standard_normal((n, m)); wg = g.standard_normal((m, e)); bg = g.standard_normal(e)
+    w1 = g.standard_normal((e, m, h)); w2 = g.standard_normal((e, h, m))
+    w3 = g.standard_normal((e, m, h)) if act == O.ACT_SWIGLU else None
+    whole = O.layer_fwd(x, wg, bg, w1, w3, w2, k, cap, act, 1, 0)
+    parts = O.layer_fwd_chunked(x, wg, bg, w1, w3, w2, k, cap, act, 1, 0, r)
+    for name in ("topk_idx", "pos", "row_of", "offsets"):
+        assert np.array_equal(whole[name], parts[name])
+    for name in ("xe", "q", "y"):
+        np.testing.assert_allclose(parts[name], whole[name], rtol=1e-12, atol=1e-12)
+    for a, b in zip(whole["saved"], parts["saved"]):
+        if a is not None:
+            np.testing.assert_allclose(b, a, rtol=1e-12, atol=1e-12)
