@@ -45,6 +45,9 @@ typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
  * or the three-matrix Mixtral FFN (MOE_ACT_SWIGLU). */
 typedef enum { MOE_ACT_RELU = 0, MOE_ACT_GELU_TANH = 1, MOE_ACT_SWIGLU = 2, MOE_ACT_GELU_ERF = 3 } moe_act_t;
 
+/* Gate-weight functions of Sec. 2.1 (values of moe_config_t.renormalize). */
+typedef enum { MOE_GATE_SOFTMAX_ALL = 0, MOE_GATE_SOFTMAX_TOPK = 1, MOE_GATE_SIGMOID = 2 } moe_gate_t;
+
 typedef struct moe_config {
   int32_t n_tokens;         /* N = B*L */
   int32_t d_model;          /* M */
@@ -54,8 +57,10 @@ typedef struct moe_config {
   int32_t capacity;         /* T, rows per expert; <= 0 means nothing is dropped (the paper's f = *) */
   int32_t dtype;            /* moe_dtype_t of activations and weights */
   int32_t act;              /* moe_act_t */
-  int32_t renormalize;      /* 1: G = Softmax(KeepTopK(H, k)) as printed in Sec. 2.1;
-                               0: softmax over all E, selected probabilities used as they are */
+  int32_t renormalize;      /* gate weights, moe_gate_t.  The k experts are always those of the k largest logits.
+                               1: G = Softmax(KeepTopK(H, k)) as printed in Sec. 2.1;
+                               0: softmax over all E, selected probabilities used as they are;
+                               2: the sigmoid gate of Sec. 2.1 (BASE, StableMoE): weight sigma(H_i) */
   int32_t add_residual;     /* 1: y = x + MoE(x) (and dx += dy) */
   int32_t accumulate_wgrad; /* 0: expert weight gradients are overwritten; 1: added to */
 } moe_config_t;
@@ -72,7 +77,7 @@ moe_status_t moe_workspace_bytes(const moe_config_t* cfg, size_t* workspace_byte
  *   logits[t,e] = fp32( sum_m x[t,m] * w_gate[m,e] + b_gate[e] ), the sum carried in fp64
  *   topk_idx[t,j] = expert with the j-th largest logit (ties: lower index), j = 0 is the largest
  *   probs = G(I): renormalize=1 -> softmax over the k kept logits, exactly 0 elsewhere;
- *                 renormalize=0 -> softmax over all E
+ *                 renormalize=0 -> softmax over all E; renormalize=2 -> sigma(logits), all E
  *   topk_w[t,j] = probs[t, topk_idx[t,j]]
  *   pos[t,j]    = slot inside the expert: choices are served rank by rank (all j=0, then j=1, ...),
  *                 tokens in order inside a rank, while the expert has fewer than T rows; else -1

@@ -81,14 +81,28 @@ def softmax_all(logits):
     return z / z.sum(axis=1, keepdims=True)
 
 
+# values of the `renormalize` argument (the gate-weight function)
+GATE_SOFTMAX_ALL = 0   # softmax over all E, the selected probabilities used as they are
+GATE_SOFTMAX_TOPK = 1  # Softmax(KeepTopK(H, k)) as printed in Sec. 2.1
+GATE_SIGMOID = 2       # the sigmoid gate of Sec. 2.1 (BASE, StableMoE): expert output scaled by sigma(H_i)
+
+
+def sigmoid(z):
+    z = np.asarray(z, np.float64)
+    return 1.0 / (1.0 + np.exp(-z))
+
+
 def gate_weights(logits, topk_idx, renormalize):
     """Gate value of every kept choice.  [N,k] float64.
 
     renormalize=1: Softmax(KeepTopK(.)) literally: the -inf entries vanish, so the
     k kept logits are soft-maxed among themselves.
-    renormalize=0: softmax over all E, the selected probabilities used as they are."""
+    renormalize=0: softmax over all E, the selected probabilities used as they are.
+    renormalize=2: sigmoid gate, sigma(H_i) of each selected logit (Sec. 2.1)."""
     l = np.asarray(logits, np.float64)
     sel = np.take_along_axis(l, topk_idx.astype(np.int64), axis=1)
+    if renormalize == GATE_SIGMOID:
+        return sigmoid(sel)
     if renormalize:
         z = np.exp(sel - sel[:, :1])       # choice 0 is the largest kept logit
         return z / z.sum(axis=1, keepdims=True)
@@ -98,7 +112,9 @@ def gate_weights(logits, topk_idx, renormalize):
 
 def gate_dense(logits, topk_idx, renormalize):
     """G(I) as an [N,E] matrix: Softmax(KeepTopK(H, k)) (zeros off the top-k) when renormalize=1,
-    the softmax over all E otherwise."""
+    the softmax over all E when 0, sigma(H) of every logit for the sigmoid gate."""
+    if renormalize == GATE_SIGMOID:
+        return sigmoid(logits)
     if not renormalize:
         return softmax_all(logits)
     g = np.zeros(np.shape(logits), np.float64)
@@ -314,6 +330,7 @@ def gate_bwd(x, w_gate, logits, topk_idx, pos, dtopk_w, renormalize, has_bias):
     g[t,e] = dw[t,j] at e = idx[t,j] for kept j, else 0.
     renormalize=0: dl = p * (g - <g,p>), p the softmax over all E.
     renormalize=1: the same formula on the k selected entries with p -> w; other entries 0.
+    renormalize=2 (sigmoid gate): dl = g * p * (1 - p), p = sigma(logits): the choices do not interact.
     Returns dlogits [N,E], dW_g [M,E], db_g [E] or None, and the gate's share of dx [N,M]."""
     n, k = topk_idx.shape
     e_cnt = logits.shape[1]
@@ -323,7 +340,10 @@ def gate_bwd(x, w_gate, logits, topk_idx, pos, dtopk_w, renormalize, has_bias):
             if pos[t, j] >= 0:
                 g[t, topk_idx[t, j]] = dtopk_w[t, j]
     p = gate_dense(logits, topk_idx, renormalize)
-    dl = p * (g - (g * p).sum(axis=1, keepdims=True))
+    if renormalize == GATE_SIGMOID:
+        dl = g * p * (1.0 - p)
+    else:
+        dl = p * (g - (g * p).sum(axis=1, keepdims=True))
     dw_gate = x.T @ dl
     db_gate = dl.sum(axis=0) if has_bias else None
     return dl, dw_gate, db_gate, dl @ w_gate.T

@@ -36,6 +36,8 @@ moe_status_t check_cfg(const moe_config_t* c) {
   REQUIRE(c->top_k <= c->n_experts, MOE_ERR_INVALID_ARG, "top_k=%d exceeds n_experts=%d", c->top_k, c->n_experts);
   REQUIRE(c->dtype == MOE_F32 || c->dtype == MOE_BF16, MOE_ERR_INVALID_ARG, "unknown dtype %d", c->dtype);
   REQUIRE(c->act >= MOE_ACT_RELU && c->act <= MOE_ACT_GELU_ERF, MOE_ERR_INVALID_ARG, "unknown activation %d", c->act);
+  REQUIRE(c->renormalize >= MOE_GATE_SOFTMAX_ALL && c->renormalize <= MOE_GATE_SIGMOID, MOE_ERR_INVALID_ARG,
+          "unknown gate-weight function %d", c->renormalize);
   REQUIRE(c->top_k <= 8, MOE_ERR_UNSUPPORTED, "top_k=%d: at most 8 is supported", c->top_k);
   REQUIRE(c->n_experts <= 256, MOE_ERR_UNSUPPORTED, "n_experts=%d: at most 256 is supported", c->n_experts);
   const int vec = c->dtype == MOE_BF16 ? 8 : 4;

@@ -245,7 +245,10 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
         atomicAdd(&hcnt[j * n_experts + be], 1);
       }
       const float mx = selv[0];
-      if (renormalize) {
+      if (renormalize == MOE_GATE_SIGMOID) {  // sigmoid gate: sigma(H_i), the choices do not interact
+        for (int e = 0; e < n_experts; ++e) l[e] = 1.0f / (1.0f + expf(-l[e]));
+        for (int j = 0; j < top_k; ++j) topk_w[(size_t)t * top_k + j] = l[sel[j]];
+      } else if (renormalize) {
         float z[kMaxK], s = 0.0f;
         for (int j = 0; j < top_k; ++j) { z[j] = expf(selv[j] - mx); s += z[j]; }
         for (int e = 0; e < n_experts; ++e) l[e] = 0.0f;
@@ -443,13 +446,14 @@ RouteBwdPlan route_bwd_plan(const moe_config_t& c) {
   return p;
 }
 
-// dlogits[t,e] = probs[t,e] * (g[t,e] - <g[t,:], probs[t,:]>), g = dtopk_w scattered to the kept choices
+// dlogits[t,e] = probs[t,e] * (g[t,e] - <g[t,:], probs[t,:]>), g = dtopk_w scattered to the kept choices;
+// sigmoid gate: dlogits[t,e] = g[t,e] * probs[t,e] * (1 - probs[t,e])
 __global__ __launch_bounds__(256) void dlogits_kernel(const float* __restrict__ probs,
                                                       const int32_t* __restrict__ topk_idx,
                                                       const int32_t* __restrict__ pos,
                                                       const float* __restrict__ dtopk_w, float* __restrict__ dl,
                                                       bf16_t* __restrict__ dlb, int n_tokens, int n_experts,
-                                                      int top_k, int ep) {
+                                                      int top_k, int ep, int gate) {
   // one thread per (token, padded expert); dlb (optional) is the bf16 copy with zero columns up to ep
   const int width = dlb != nullptr ? ep : n_experts;
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -467,7 +471,8 @@ __global__ __launch_bounds__(256) void dlogits_kernel(const float* __restrict__ 
         if (ej == e) g = d;
       }
     }
-    v = probs[(size_t)t * n_experts + e] * (g - s);
+    const float pe = probs[(size_t)t * n_experts + e];
+    v = gate == MOE_GATE_SIGMOID ? g * pe * (1.0f - pe) : pe * (g - s);
     dl[(size_t)t * n_experts + e] = v;
   }
   if (dlb != nullptr) dlb[i] = f32_to_bf16(v);
@@ -646,7 +651,7 @@ moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_g
   float* bpart = reinterpret_cast<float*>(w + p.off_bpart);
   const size_t ne = (size_t)c.n_tokens * c.n_experts;
   hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
-                     dl, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0);
+                     dl, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0, c.renormalize);
   MOE_CHECK_LAUNCH();
   hipLaunchKernelGGL(gate_dx_kernel<T>, dim3(ceil_div(c.n_tokens, kDxTokens), ceil_div(c.d_model, 256 * V)), dim3(256),
                      (size_t)kDxTokens * c.n_experts * sizeof(float), s, dl, (const T*)w_gate, (T*)dx, c.n_tokens,
@@ -683,7 +688,7 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
   int32_t* tok = reinterpret_cast<int32_t*>(w + p.off_tok);
   const size_t ne = (size_t)c.n_tokens * p.ep;
   hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
-                     dl, dlb, c.n_tokens, c.n_experts, c.top_k, p.ep);
+                     dl, dlb, c.n_tokens, c.n_experts, c.top_k, p.ep, c.renormalize);
   MOE_CHECK_LAUNCH();
   const int npad = c.d_model * p.ep > p.nsplit + 1 ? c.d_model * p.ep : p.nsplit + 1;
   hipLaunchKernelGGL(pad_gate_kernel, dim3(ceil_div(npad, 256)), dim3(256), 0, s, (const bf16_t*)w_gate, wgp, tok,

@@ -36,6 +36,9 @@ CASES = {
     "rows_2waves_f32": S.scaled(W["tiny"], N=200, M=320, H=64, E=4, k=2, seed=29),
     # M and H multiples of 32 but not of 64: the 32-k pipeline of the MFMA GEMM (the others take 64-k batches)
     "k32_pipeline": S.scaled(W["mixtral"], N=600, M=160, H=224, E=4, seed=30),
+    # sigmoid gate (Sec. 2.1): weights sigma(H_i), no normalisation over the choices
+    "sigmoid_glu": S.scaled(W["mixtral"], N=900, M=128, H=192, E=8, k=2, renormalize=2, seed=31),
+    "sigmoid_f32_drops": S.scaled(W["tiny"], N=400, M=64, H=96, E=6, k=3, f=1.0, renormalize=2, seed=32),
 }
 
 
@@ -168,7 +171,7 @@ def test_route_bwd(name, solved):
             if fwd["pos"][t, j] >= 0:
                 g[t, fwd["topk_idx"][t, j]] = dtw32[t, j]
     p = probs32.astype(np.float64)
-    dl = p * (g - (g * p).sum(1, keepdims=True))
+    dl = g * p * (1.0 - p) if w.renormalize == 2 else p * (g - (g * p).sum(1, keepdims=True))
     tol = TOL[w.dtype]
     assert rel_err(to_np(b.dw_gate), f["x"].T @ dl) <= tol
     assert rel_err(to_np(b.dx), S.to_f64(base) + dl @ f["w_gate"].T) <= tol

@@ -339,7 +339,8 @@ def _loss_and_grads(params, dy, k, cap, act, renorm, resid):
 
 @pytest.mark.parametrize("act,k,cap,renorm,resid", [
     (O.ACT_RELU, 1, 5, 0, 0), (O.ACT_GELU_TANH, 2, 7, 0, 1), (O.ACT_SWIGLU, 2, 0, 1, 0),
-    (O.ACT_SWIGLU, 3, 8, 0, 0), (O.ACT_GELU_ERF, 2, 0, 1, 1), (O.ACT_GELU_TANH, 1, 0, 1, 0)])
+    (O.ACT_SWIGLU, 3, 8, 0, 0), (O.ACT_GELU_ERF, 2, 0, 1, 1), (O.ACT_GELU_TANH, 1, 0, 1, 0),
+    (O.ACT_SWIGLU, 2, 0, O.GATE_SIGMOID, 0), (O.ACT_GELU_TANH, 3, 6, O.GATE_SIGMOID, 1)])
 def test_layer_backward_matches_central_differences(act, k, cap, renorm, resid):
     r = rng(70 + act + 10 * k)
     n, m, h, e = 14, 4, 5, 4
@@ -459,3 +460,22 @@ def test_chunked_layer_equals_whole_layer(act, k, cap, r):
     for a, b in zip(whole["saved"], parts["saved"]):
         if a is not None:
             np.testing.assert_allclose(b, a, rtol=1e-12, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- sigmoid gate (Sec. 2.1)
+
+def test_sigmoid_gate_values():
+    """Sec. 2.1: with the sigmoid gate the expert output is scaled by sigma(H_i); closed-form values, and the
+    choices stay those of the k largest logits."""
+    logits = np.array([[0.0, math.log(3.0), -math.log(3.0), 40.0], [-40.0, 2.0, 1.0, 0.5]])
+    idx = O.keep_top_k(logits, 2)
+    assert idx.tolist() == [[3, 1], [1, 2]]
+    w = O.gate_weights(logits, idx, O.GATE_SIGMOID)
+    want = [[1.0 / (1.0 + math.exp(-40.0)), 0.75], [1.0 / (1.0 + math.exp(-2.0)), 1.0 / (1.0 + math.exp(-1.0))]]
+    np.testing.assert_allclose(w, want, rtol=1e-15)
+    dense = O.gate_dense(logits, idx, O.GATE_SIGMOID)
+    np.testing.assert_allclose(dense[0], [0.5, 0.75, 0.25, want[0][0]], rtol=1e-15)
+    # unlike the softmax gates the weights of a token do not sum to one and do not depend on each other
+    l2 = logits.copy(); l2[0, 1] += 1.0
+    w2 = O.gate_weights(l2, O.keep_top_k(l2, 2), O.GATE_SIGMOID)
+    assert w2[0, 0] == w[0, 0] and w2[0, 1] > w[0, 1]
