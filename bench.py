@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--chunks", type=int, default=0,
                     help="also time the layer run in this many chunks (moe_layer_fwd_chunked / moe_layer_bwd_chunked, "
                          "dispatch of the next chunk on a second stream); reported beside the headline figure")
+    ap.add_argument("--fit-expert-model", action="store_true",
+                    help="time the expert FFN on 1/r of the rows of every expert, r = 1, 2, 4, 8, 16, and fit the linear model "
+                         "t = alpha + (n / r) * beta of FSMoE Sec. 4.1; reports the fit and what Algorithm 1 picks on one GPU")
     ap.add_argument("--calibrate-gemm", action="store_true",
                     help="also time the vendor library's plain bf16 GEMM (torch.matmul) for about a second per layout on this box: "
                          "context for the MFMA roofline fraction, since the sustained clock differs from box to box")
@@ -72,6 +75,37 @@ def library_gemm_reference(torch, m=32768, n=4096, k=14336, secs=1.0):
         out[name] = round(sum(half) / len(half), 1)
         del b, bb, c
     return {"what": f"torch.matmul bf16 {m}x{n}x{k}, sustained, TFLOP/s", **out}
+
+
+def fit_expert_model(torch, cfg, w, d, b, xe, a1, a3, hh, count, timed, reps, fwd_flop):
+    """FSMoE Sec. 4.1: t_exp,r = alpha_exp + (n_exp / r) * beta_exp, fitted by least squares on the measured time of
+    moe_expert_ffn_fwd / _bwd over the first 1/r of the rows of every expert (n_exp in TFLOP of the whole layer)."""
+    import numpy as np
+    import paper_2501_10714_amd as moe
+    res = {}
+    rs = [1, 2, 4, 8, 16]
+    for phase, flop in (("fwd", fwd_flop), ("bwd", 2 * fwd_flop)):
+        ts = []
+        for r in rs:
+            cnt = torch.div(count, r, rounding_mode="floor")
+            off = torch.zeros(w.E + 1, dtype=torch.int32, device="cuda")
+            off[1:] = torch.cumsum(cnt, 0)
+            if phase == "fwd":
+                ts.append(timed(lambda: moe.moe_expert_ffn_fwd(cfg, xe, off, d["w1"], d["w3"], d["w2"], b.q, b.a1, b.a3, b.hh, b.ws), reps))
+            else:
+                ts.append(timed(lambda: moe.moe_expert_ffn_bwd(cfg, b.dq, xe, off, d["w1"], d["w3"], d["w2"], a1, a3, hh, b.dxe,
+                                                               b.dw1, b.dw3, b.dw2, b.ws), reps))
+        x = np.array([flop / 1e12 / r for r in rs])
+        y = np.array(ts)
+        beta, alpha = np.polyfit(x, y, 1)
+        resid = y - (alpha + beta * x)
+        m = moe.PipelineModel(0, 0, 0, 0, 0, 0, 0, 0, 0, max(alpha, 0.0), beta, flop / 1e12, 0.0)
+        r_opt, t_opt, case = moe.moe_find_pipeline_degree(m, 16)
+        res[phase] = {"r": rs, "ms": [round(t, 3) for t in ts], "alpha_ms": round(float(alpha), 4),
+                      "beta_ms_per_tflop": round(float(beta), 4), "n_tflop": round(flop / 1e12, 3),
+                      "max_abs_residual_ms": round(float(np.abs(resid).max()), 4),
+                      "algorithm1_one_gpu": {"r": r_opt, "t_ms": round(t_opt, 3), "case": case}}
+    return res
 
 
 def device_inputs(w, torch):
@@ -192,6 +226,8 @@ def main():
            "expert_gemm_tflops": round(achieved, 1), "roofline": roofline}
     if library_gemm is not None:
         out["library_gemm_reference"] = library_gemm
+    if args.fit_expert_model:
+        out["expert_model"] = fit_expert_model(torch, cfg, w, d, b, xe, a1, a3, hh, torch.from_numpy(count).to("cuda"), timed, reps, flop_fwd)
     if args.chunks > 1:
         aux = torch.cuda.Stream()
 

@@ -192,6 +192,33 @@ typedef enum {
 } moe_saved_tensor_t;
 moe_status_t moe_saved_offset(const moe_config_t* cfg, int32_t which, size_t* byte_offset, size_t* n_bytes);
 
+/* ---- pipeline degree (Sec. 4): host functions, no GPU work ------------------------------------------
+ * Linear performance models of Sec. 4.1, Eq. (1): one of r chunks of AlltoAll (dispatch or combine),
+ * ESP-AllGather, ESP-ReduceScatter and expert computation takes alpha + (n / r) * beta; n is the message
+ * size or the amount of computation of the whole layer, alpha the start-up time.  t_gar: time of the
+ * Gradient-AllReduce to hide behind the layer (0 in the forward phase, Sec. 4.4).  All >= 0, any one unit
+ * of time.  On one GPU the three communication models are zero; alpha_exp, beta_exp come from timing the
+ * expert FFN at several chunk sizes (bench.py --fit-expert-model). */
+typedef struct moe_pipeline_model {
+  double alpha_a2a, beta_a2a, n_a2a;
+  double alpha_ag, beta_ag, n_ag;
+  double alpha_rs, beta_rs, n_rs;
+  double alpha_exp, beta_exp, n_exp;
+  double t_gar;
+} moe_pipeline_model_t;
+
+/* Time of the MoE layer at pipeline degree r >= 1 (Sec. 4.2): the conditions Q1..Q7 decide which of the
+ * four cases r falls into (every r falls into exactly one), the result is that case's closed form
+ * t^moe_1..4.  *which_case (may be NULL) receives 1..4.  NaN for an invalid model or r < 1. */
+double moe_pipeline_time(const moe_pipeline_model_t* model, double r, int32_t* which_case);
+
+/* Algorithm 1 (FindOptimalPipelineDegree) over the integer degrees 1..r_max: for each case the minimum
+ * of its closed form over the degrees that satisfy the case's condition, then the smallest of the four
+ * minima; ties go to the smaller degree.  Enumeration replaces the paper's SLSQP solves on a real r.
+ * out: *r; *t_moe and *which_case may be NULL.  MOE_ERR_INVALID_ARG for an invalid model or r_max < 1. */
+moe_status_t moe_find_pipeline_degree(const moe_pipeline_model_t* model, int32_t r_max, int32_t* r, double* t_moe,
+                                      int32_t* which_case);
+
 /* Message of the last failed call on this host thread ("" if none).  Static storage. */
 const char* moe_last_error(void);
 

@@ -21,7 +21,7 @@ _LIB = None
 ENTRY_POINTS = ["moe_capacity", "moe_workspace_bytes", "moe_route", "moe_dispatch", "moe_dispatch_bwd",
                 "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_combine", "moe_combine_bwd", "moe_route_bwd",
                 "moe_layer_fwd", "moe_layer_bwd", "moe_layer_fwd_chunked", "moe_layer_bwd_chunked", "moe_saved_offset",
-                "moe_last_error"]
+                "moe_pipeline_time", "moe_find_pipeline_degree", "moe_last_error"]
 MAX_CHUNKS = 16  # MOE_MAX_CHUNKS
 
 
@@ -54,7 +54,7 @@ def load():
         lib.moe_capacity.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_double]
         lib.moe_last_error.restype = C.c_char_p
         for name in ENTRY_POINTS:
-            if name not in ("moe_capacity", "moe_last_error"):
+            if name not in ("moe_capacity", "moe_last_error", "moe_pipeline_time"):
                 getattr(lib, name).restype = C.c_int32
         _LIB = lib
     return _LIB
@@ -168,3 +168,25 @@ def moe_layer_bwd_chunked(cfg, dy, x, w_gate, w1, w3, w2, saved, dx, dw_gate, db
     _check(load().moe_layer_bwd_chunked(C.byref(cfg), _p(dy), _p(x), _p(w_gate), _p(w1), _p(w3), _p(w2), _p(saved),
                                         _sz(saved), _p(dx), _p(dw_gate), _p(db_gate), _p(dw1), _p(dw3), _p(dw2), _p(ws),
                                         _sz(ws), C.c_int32(n_chunks), _stream()))
+
+
+class PipelineModel(C.Structure):
+    """moe_pipeline_model_t: the linear performance models of FSMoE Sec. 4.1 and the Gradient-AllReduce time."""
+    _fields_ = [(n, C.c_double) for n in ("alpha_a2a", "beta_a2a", "n_a2a", "alpha_ag", "beta_ag", "n_ag", "alpha_rs",
+                                          "beta_rs", "n_rs", "alpha_exp", "beta_exp", "n_exp", "t_gar")]
+
+
+def moe_pipeline_time(model, r):
+    """(t_moe, case) at pipeline degree r; host function."""
+    lib = load()
+    lib.moe_pipeline_time.restype = C.c_double
+    which = C.c_int32(0)
+    t = lib.moe_pipeline_time(C.byref(model), C.c_double(r), C.byref(which))
+    return float(t), int(which.value)
+
+
+def moe_find_pipeline_degree(model, r_max):
+    """(r, t_moe, case) of Algorithm 1 over the degrees 1..r_max; host function."""
+    r, which, t = C.c_int32(0), C.c_int32(0), C.c_double(0.0)
+    _check(load().moe_find_pipeline_degree(C.byref(model), C.c_int32(r_max), C.byref(r), C.byref(t), C.byref(which)))
+    return int(r.value), float(t.value), int(which.value)
