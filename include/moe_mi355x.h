@@ -167,8 +167,8 @@ moe_status_t moe_layer_bwd(const moe_config_t* cfg, const void* dy, const void* 
  * n_chunks: 1 .. MOE_MAX_CHUNKS (1 = moe_layer_fwd).  aux_stream: NULL, or a second hipStream_t on which
  * the dispatch of chunk c+1 is enqueued while chunk c is in the expert FFN on `stream`; on return all work
  * of aux_stream is ordered before what the caller enqueues next on `stream` (the library records and
- * waits on events of its own; it creates them once, on first use).  Calls that overlap on one device
- * must not share aux_stream.  Other arguments and errors as moe_layer_fwd. */
+ * waits on events that it creates for the call and destroys before it returns).  Other arguments and
+ * errors as moe_layer_fwd. */
 #define MOE_MAX_CHUNKS 16
 moe_status_t moe_layer_fwd_chunked(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
                                    const void* w1, const void* w3, const void* w2, void* y, void* saved,

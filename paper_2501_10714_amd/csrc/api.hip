@@ -107,16 +107,6 @@ size_t workspace_bytes(const moe_config_t& c) {
   return chunk_bounds_offset(c) + align_up((size_t)2 * MOE_MAX_CHUNKS * c.n_experts * sizeof(int32_t), 256);
 }
 
-// Events that order the two streams of the chunked forward pass; created on first use, never destroyed.
-hipEvent_t* chunk_events() {
-  static hipEvent_t ev[MOE_MAX_CHUNKS + 1];
-  static bool ok = [] {
-    for (auto& e : ev)
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return false;
-    return true;
-  }();
-  return ok ? ev : nullptr;
-}
 
 inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
 
@@ -273,12 +263,21 @@ static moe_status_t layer_fwd_impl(const char* fn, const moe_config_t* cfg, cons
     st = launch_chunk_bounds(*cfg, offsets, r, begin, end, s);
     if (st != MOE_OK) return st;
     hipStream_t aux = as_stream(aux_stream);
+    // events of this call only (two calls on different stream pairs may run at once); an event may be
+    // destroyed as soon as the work that waits on it has been enqueued
+    struct Events {
+      hipEvent_t e[MOE_MAX_CHUNKS + 1];
+      int n = 0;
+      ~Events() { for (int i = 0; i < n; ++i) (void)hipEventDestroy(e[i]); }
+    } evs;
     hipEvent_t* ev = nullptr;
     if (aux_stream != nullptr && aux != s) {
-      ev = chunk_events();
-      REQUIRE(ev != nullptr, MOE_ERR_DEVICE, "%s: could not create events", fn);
-      REQUIRE(hipEventRecord(ev[MOE_MAX_CHUNKS], s) == hipSuccess && hipStreamWaitEvent(aux, ev[MOE_MAX_CHUNKS], 0) == hipSuccess,
-              MOE_ERR_DEVICE, "%s: stream ordering failed", fn);
+      for (; evs.n < r + 1; ++evs.n)
+        REQUIRE(hipEventCreateWithFlags(&evs.e[evs.n], hipEventDisableTiming) == hipSuccess, MOE_ERR_DEVICE,
+                "%s: could not create an event", fn);
+      ev = evs.e;
+      REQUIRE(hipEventRecord(ev[r], s) == hipSuccess && hipStreamWaitEvent(aux, ev[r], 0) == hipSuccess, MOE_ERR_DEVICE,
+              "%s: stream ordering failed", fn);
     }
     for (int c = 0; c < r; ++c) {
       const int32_t* bc = begin + (size_t)c * cfg->n_experts;

@@ -503,11 +503,6 @@ __global__ __launch_bounds__(256) void gate_dw_reduce_bf16_kernel(const bf16_t* 
     for (int g = 0; g < nsplit; ++g) s += bf16_to_f32(part[((size_t)g * d_model + m) * ep + e]);
     dw_gate[i] = f32_to_bf16(s);
   }
-  if (db_gate != nullptr && i < n_experts) {
-    float s = 0.0f;
-    for (int tl = 0; tl < ntile; ++tl) s += bpart[(size_t)tl * n_experts + i];
-    db_gate[i] = s;
-  }
 }
 
 // dx[t, m..m+V) += sum_e dl[t,e] * W_g[m.., e]; a thread owns one 16-byte column chunk for kDxTokens tokens
@@ -608,15 +603,40 @@ __global__ __launch_bounds__(kDwThreads) void gate_dw_partial_kernel(const T* __
   }
 }
 
+// db_g = column sums of dlogits, in two fixed-order steps (so runs repeat): per tile of kDwTokens tokens,
+// 256 / E token lanes per column summed in lane order; then the tiles per column, 256 lanes and a tree.
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __restrict__ dl, float* __restrict__ bpart,
                                                              int n_tokens, int n_experts) {
-  // block = one token tile; thread e sums its column over the tile in token order
+  __shared__ float sh[256];
+  const int lanes = 256 / n_experts;  // token lanes per column (n_experts <= 256)
+  const int e = threadIdx.x % n_experts, sub = threadIdx.x / n_experts;
   const int t0 = blockIdx.x * kDwTokens;
-  for (int e = threadIdx.x; e < n_experts; e += 256) {
-    float s = 0.0f;
-    for (int tk = 0; tk < kDwTokens && t0 + tk < n_tokens; ++tk) s += dl[(size_t)(t0 + tk) * n_experts + e];
-    bpart[(size_t)blockIdx.x * n_experts + e] = s;
+  float s = 0.0f;
+  if (sub < lanes)
+    for (int tk = sub; tk < kDwTokens && t0 + tk < n_tokens; tk += lanes) s += dl[(size_t)(t0 + tk) * n_experts + e];
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  if (sub == 0) {
+    float v = 0.0f;
+    for (int l = 0; l < lanes; ++l) v += sh[l * n_experts + e];
+    bpart[(size_t)blockIdx.x * n_experts + e] = v;
   }
+}
+
+// block e: db_gate[e] = sum over tiles of bpart[tile][e]
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ bpart, float* __restrict__ db_gate,
+                                                           int ntile, int n_experts) {
+  __shared__ float sh[256];
+  const int e = blockIdx.x;
+  float s = 0.0f;
+  for (int tl = threadIdx.x; tl < ntile; tl += 256) s += bpart[(size_t)tl * n_experts + e];
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) db_gate[e] = sh[0];
 }
 
 template <typename T>
@@ -630,11 +650,6 @@ __global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __rest
     float s = 0.0f;
     for (int tl = 0; tl < ntile; ++tl) s += part[(size_t)tl * n + i];
     Elem<T>::st(dw_gate + i, s);
-  }
-  if (db_gate != nullptr && i < n_experts) {
-    float s = 0.0f;
-    for (int tl = 0; tl < ntile; ++tl) s += bpart[(size_t)tl * n_experts + i];
-    db_gate[i] = s;
   }
 }
 
@@ -663,6 +678,8 @@ moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_g
   MOE_CHECK_LAUNCH();
   if (db_gate != nullptr) {
     hipLaunchKernelGGL(colsum_partial_kernel, dim3(p.ntile), dim3(256), 0, s, dl, bpart, c.n_tokens, c.n_experts);
+    MOE_CHECK_LAUNCH();
+    hipLaunchKernelGGL(colsum_final_kernel, dim3(c.n_experts), dim3(256), 0, s, bpart, db_gate, p.ntile, c.n_experts);
     MOE_CHECK_LAUNCH();
   }
   hipLaunchKernelGGL(gate_dw_reduce_kernel<T>, dim3(ceil_div(c.d_model * c.n_experts, 256)), dim3(256), 0, s, part, bpart,
@@ -717,6 +734,8 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
   }
   if (db_gate != nullptr) {
     hipLaunchKernelGGL(colsum_partial_kernel, dim3(p.ntile), dim3(256), 0, s, dl, bpart, c.n_tokens, c.n_experts);
+    MOE_CHECK_LAUNCH();
+    hipLaunchKernelGGL(colsum_final_kernel, dim3(c.n_experts), dim3(256), 0, s, bpart, db_gate, p.ntile, c.n_experts);
     MOE_CHECK_LAUNCH();
   }
   hipLaunchKernelGGL(gate_dw_reduce_bf16_kernel, dim3(ceil_div(c.d_model * c.n_experts, 256)), dim3(256), 0, s, part,
