@@ -192,6 +192,27 @@ typedef enum {
 } moe_saved_tensor_t;
 moe_status_t moe_saved_offset(const moe_config_t* cfg, int32_t which, size_t* byte_offset, size_t* n_bytes);
 
+/* The noisy gate of Sec. 2.1: H(I) = I.W_g (+ b_g) + noise * Softplus(I.W_noise), then everything moe_route
+ * does with H in place of I.W_g.  The standard-normal draws are an input, so the call is a function of its
+ * arguments.  Both products are accumulated in fp64 and rounded once to fp32; H is formed from the two fp32
+ * tensors in fp64 and rounded once.
+ * in : as moe_route, plus w_noise [M,E] dtype and noise [N,E] f32.
+ * out: as moe_route (logits = H), plus noise_logits [N,E] f32 = I.W_noise (moe_route_noisy_bwd needs it). */
+moe_status_t moe_route_noisy(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
+                             const void* w_noise, const float* noise, float* logits, float* noise_logits, float* probs,
+                             int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
+                             int32_t* offsets, int32_t* src_of_row, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of the noisy gate, routing decision and noise draws held fixed: with dH = dlogits as in
+ * moe_route_bwd, dw_gate = x^T.dH, db_gate = column sums of dH, and for the noise product
+ * dN = dH * noise * sigma(noise_logits): dw_noise = x^T.dN; dx += dH.W_g^T + dN.W_noise^T (ACCUMULATED INTO).
+ * out: dw_gate, dw_noise [M,E] dtype, db_gate [E] f32 or NULL. */
+moe_status_t moe_route_noisy_bwd(const moe_config_t* cfg, const void* x, const void* w_gate, const void* w_noise,
+                                 const float* noise, const float* noise_logits, const float* probs,
+                                 const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                                 float* db_gate, void* dw_noise, void* dx, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
 /* ---- pipeline degree (Sec. 4): host functions, no GPU work ------------------------------------------
  * Linear performance models of Sec. 4.1, Eq. (1): one of r chunks of AlltoAll (dispatch or combine),
  * ESP-AllGather, ESP-ReduceScatter and expert computation takes alpha + (n / r) * beta; n is the message

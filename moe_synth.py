@@ -89,7 +89,8 @@ def to_f64(a: np.ndarray) -> np.ndarray:
 
 # ----------------------------------------------------------------------------- draws
 
-_TENSOR_IDS = {"x": 1, "w_gate": 2, "b_gate": 3, "w1": 4, "w3": 5, "w2": 6, "dy": 7, "perm": 8, "sample": 9}
+_TENSOR_IDS = {"x": 1, "w_gate": 2, "b_gate": 3, "w1": 4, "w3": 5, "w2": 6, "dy": 7, "perm": 8, "sample": 9,
+               "w_noise": 10, "noise": 11, "dtopk_w": 12}
 
 
 def _rng(seed: int, tensor: str, part: int = 0) -> np.random.Generator:
@@ -117,6 +118,21 @@ def draw_dy(w: Workload) -> np.ndarray:
 
 def draw_w_gate(w: Workload) -> np.ndarray:
     return _store(_normal(w.seed, "w_gate", (w.M, w.E), 0.02), w.dtype)
+
+
+def draw_w_noise(w: Workload) -> np.ndarray:
+    """W_noise of the noisy gate, like W_g."""
+    return _store(_normal(w.seed, "w_noise", (w.M, w.E), 0.02), w.dtype)
+
+
+def draw_noise(w: Workload) -> np.ndarray:
+    """The standard-normal draws of the noisy gate, fp32 [N,E] (an input of the path)."""
+    return _normal(w.seed, "noise", (w.N, w.E), 1.0)
+
+
+def draw_dtopk_w(w: Workload) -> np.ndarray:
+    """An upstream gradient for the gate weights, fp32 [N,k] (for gate-only backward checks)."""
+    return _normal(w.seed, "dtopk_w", (w.N, w.k), 1.0)
 
 
 def draw_b_gate(w: Workload):

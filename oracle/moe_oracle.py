@@ -58,6 +58,24 @@ def gate_logits(x, w_gate, b_gate=None, logit_dtype=np.float32):
     return h.astype(logit_dtype)
 
 
+def softplus(z):
+    """Softplus(z) = ln(1 + e^z), evaluated as logaddexp(0, z) (no overflow for large |z|)."""
+    return np.logaddexp(0.0, np.asarray(z, np.float64))
+
+
+def gate_logits_noisy(x, w_gate, b_gate, w_noise, noise, logit_dtype=np.float32):
+    """The noisy gate of Sec. 2.1: H(I)_i = (I.W_g)_i + N(0,1) * Softplus((I.W_noise)_i), with the standard-normal
+    draws passed in (`noise`, [N,E]) so that the result is a function of its arguments.
+
+    Reading of the precision (the paper gives none): both products are accumulated in fp64 and rounded once to
+    fp32 (they are outputs of the path: the second one is kept for the backward pass); H is then formed from
+    those two fp32 tensors in fp64 and rounded once to fp32.  Returns (H, I.W_noise), both [N,E]."""
+    clean = gate_logits(x, w_gate, b_gate, logit_dtype)
+    nl = gate_logits(x, w_noise, None, logit_dtype)
+    h = clean.astype(np.float64) + np.asarray(noise, np.float64) * softplus(nl)
+    return h.astype(logit_dtype), nl
+
+
 def keep_top_k(logits, k):
     """Indices of the k largest logits of every token, largest first.  [N,k] int32.
 
@@ -347,6 +365,27 @@ def gate_bwd(x, w_gate, logits, topk_idx, pos, dtopk_w, renormalize, has_bias):
     dw_gate = x.T @ dl
     db_gate = dl.sum(axis=0) if has_bias else None
     return dl, dw_gate, db_gate, dl @ w_gate.T
+
+
+def route_noisy(x, w_gate, b_gate, w_noise, noise, k, cap, renormalize, logit_dtype=np.float32):
+    """route() with the noisy logits of Sec. 2.1 in place of I.W_g."""
+    logits, nl = gate_logits_noisy(x, w_gate, b_gate, w_noise, noise, logit_dtype)
+    idx = keep_top_k(logits, k)
+    w = gate_weights(logits, idx, renormalize)
+    pos, count, offsets, row_of, src_of_row = assign_positions(idx, w_gate.shape[1], cap)
+    return dict(logits=logits, noise_logits=nl, probs=gate_dense(logits, idx, renormalize), topk_idx=idx, topk_w=w,
+                pos=pos, count=count, offsets=offsets, row_of=row_of, src_of_row=src_of_row)
+
+
+def gate_bwd_noisy(x, w_gate, w_noise, noise, noise_logits, logits, topk_idx, pos, dtopk_w, renormalize, has_bias):
+    """Adjoint of the noisy gate with the routing decision and the noise draws held fixed.
+
+    dH as in gate_bwd.  H = I.W_g + b + noise * Softplus(I.W_noise), Softplus' = sigma, so
+    d(I.W_noise) = dH * noise * sigma(I.W_noise); each product then contributes x^T.d(.) to its weight and
+    d(.).W^T to dx.  Returns dH, dW_g, db_g or None, dW_noise, and the gate's share of dx."""
+    dl, dw_gate, db_gate, dx = gate_bwd(x, w_gate, logits, topk_idx, pos, dtopk_w, renormalize, has_bias)
+    dn = dl * np.asarray(noise, np.float64) * sigmoid(noise_logits)
+    return dl, dw_gate, db_gate, x.T @ dn, dx + dn @ w_noise.T
 
 
 # ----------------------------------------------------------------------------- whole layer

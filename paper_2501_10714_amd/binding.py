@@ -21,7 +21,7 @@ _LIB = None
 ENTRY_POINTS = ["moe_capacity", "moe_workspace_bytes", "moe_route", "moe_dispatch", "moe_dispatch_bwd",
                 "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_combine", "moe_combine_bwd", "moe_route_bwd",
                 "moe_layer_fwd", "moe_layer_bwd", "moe_layer_fwd_chunked", "moe_layer_bwd_chunked", "moe_saved_offset",
-                "moe_pipeline_time", "moe_find_pipeline_degree", "moe_last_error"]
+                "moe_pipeline_time", "moe_find_pipeline_degree", "moe_route_noisy", "moe_route_noisy_bwd", "moe_last_error"]
 MAX_CHUNKS = 16  # MOE_MAX_CHUNKS
 
 
@@ -190,3 +190,18 @@ def moe_find_pipeline_degree(model, r_max):
     r, which, t = C.c_int32(0), C.c_int32(0), C.c_double(0.0)
     _check(load().moe_find_pipeline_degree(C.byref(model), C.c_int32(r_max), C.byref(r), C.byref(t), C.byref(which)))
     return int(r.value), float(t.value), int(which.value)
+
+
+
+def moe_route_noisy(cfg, x, w_gate, b_gate, w_noise, noise, logits, noise_logits, probs, topk_idx, topk_w, pos, row_of,
+                    count, offsets, src_of_row, ws):
+    _check(load().moe_route_noisy(C.byref(cfg), _p(x), _p(w_gate), _p(b_gate), _p(w_noise), _p(noise), _p(logits),
+                                  _p(noise_logits), _p(probs), _p(topk_idx), _p(topk_w), _p(pos), _p(row_of), _p(count),
+                                  _p(offsets), _p(src_of_row), _p(ws), _sz(ws), _stream()))
+
+
+def moe_route_noisy_bwd(cfg, x, w_gate, w_noise, noise, noise_logits, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate,
+                        dw_noise, dx, ws):
+    _check(load().moe_route_noisy_bwd(C.byref(cfg), _p(x), _p(w_gate), _p(w_noise), _p(noise), _p(noise_logits),
+                                      _p(probs), _p(topk_idx), _p(pos), _p(dtopk_w), _p(dw_gate), _p(db_gate),
+                                      _p(dw_noise), _p(dx), _p(ws), _sz(ws), _stream()))

@@ -163,6 +163,33 @@ moe_status_t moe_route(const moe_config_t* cfg, const void* x, const void* w_gat
                       workspace, as_stream(stream));
 }
 
+moe_status_t moe_route_noisy(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
+                             const void* w_noise, const float* noise, float* logits, float* noise_logits, float* probs,
+                             int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
+                             int32_t* offsets, int32_t* src_of_row, void* workspace, size_t workspace_bytes_,
+                             void* stream) {
+  CHECK_CFG(cfg);
+  NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(w_noise); NOT_NULL(noise); NOT_NULL(logits); NOT_NULL(noise_logits);
+  NOT_NULL(probs); NOT_NULL(topk_idx); NOT_NULL(topk_w); NOT_NULL(pos); NOT_NULL(row_of); NOT_NULL(count);
+  NOT_NULL(offsets); NOT_NULL(src_of_row);
+  CHECK_WS(cfg, workspace, workspace_bytes_);
+  return launch_route_noisy(*cfg, x, w_gate, b_gate, w_noise, noise, logits, noise_logits, probs, topk_idx, topk_w, pos,
+                            row_of, count, offsets, src_of_row, workspace, as_stream(stream));
+}
+
+moe_status_t moe_route_noisy_bwd(const moe_config_t* cfg, const void* x, const void* w_gate, const void* w_noise,
+                                 const float* noise, const float* noise_logits, const float* probs,
+                                 const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                                 float* db_gate, void* dw_noise, void* dx, void* workspace, size_t workspace_bytes_,
+                                 void* stream) {
+  CHECK_CFG(cfg);
+  NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(w_noise); NOT_NULL(noise); NOT_NULL(noise_logits); NOT_NULL(probs);
+  NOT_NULL(topk_idx); NOT_NULL(pos); NOT_NULL(dtopk_w); NOT_NULL(dw_gate); NOT_NULL(dw_noise); NOT_NULL(dx);
+  CHECK_WS(cfg, workspace, workspace_bytes_);
+  return launch_route_noisy_bwd(*cfg, x, w_gate, w_noise, noise, noise_logits, probs, topk_idx, pos, dtopk_w, dw_gate,
+                                db_gate, dw_noise, dx, workspace, as_stream(stream));
+}
+
 moe_status_t moe_dispatch(const moe_config_t* cfg, const void* x, const int32_t* row_of, void* xe, void* stream) {
   CHECK_CFG(cfg);
   NOT_NULL(x); NOT_NULL(row_of); NOT_NULL(xe);

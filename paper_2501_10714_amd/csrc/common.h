@@ -111,6 +111,14 @@ size_t route_workspace_bytes(const moe_config_t& c);
 moe_status_t launch_route(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
                           float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
                           int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s);
+moe_status_t launch_route_noisy(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate,
+                                const void* w_noise, const float* noise, float* logits, float* noise_logits, float* probs,
+                                int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
+                                int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s);
+moe_status_t launch_route_noisy_bwd(const moe_config_t& c, const void* x, const void* w_gate, const void* w_noise,
+                                    const float* noise, const float* noise_logits, const float* probs,
+                                    const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                                    float* db_gate, void* dw_noise, void* dx, void* ws, hipStream_t s);
 size_t route_bwd_workspace_bytes(const moe_config_t& c);
 moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                               const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,

@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
     const T* __restrict__ x, const double* __restrict__ wd, const float* __restrict__ b_gate,
     float* __restrict__ logits, float* __restrict__ probs, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     int32_t* __restrict__ hist, int n_tokens, int d_model, int n_experts, int top_k, int renormalize, int ep, int nkc,
-    int nb) {
+    int nb, const float* __restrict__ noise, const float* __restrict__ noise_logits) {
   constexpr int EE = 8 * NEG;         // experts per pass
   constexpr int NKS = 32 / NEG;       // K slices
   constexpr int KPS = kKC / NKS;      // k per slice and chunk
@@ -211,7 +211,16 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
       if (ec + e < n_experts) {
         double v = red[e * kTile + tk];
         if (b_gate != nullptr) v += (double)b_gate[ec + e];
-        lg[tk * lgs + ec + e] = (float)v;
+        float f = (float)v;
+        if (noise != nullptr && t0 + tk < n_tokens) {
+          // noisy gate (Sec. 2.1): H = I.W_g + noise * Softplus(I.W_noise), formed in fp64 from the two fp32
+          // products and rounded once
+          const size_t gi = (size_t)(t0 + tk) * n_experts + ec + e;
+          const double z = (double)noise_logits[gi];
+          const double sp = z > 0.0 ? z + log1p(exp(-z)) : log1p(exp(z));
+          f = (float)((double)f + (double)noise[gi] * sp);
+        }
+        lg[tk * lgs + ec + e] = f;
       }
     }
     __syncthreads();
@@ -369,7 +378,8 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t* __restric
 
 template <typename T, int NEG>
 void launch_gate(const moe_config_t& c, const RoutePlan& p, const void* x, const double* wd, const float* b_gate,
-                 float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* hist, hipStream_t s) {
+                 float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* hist, const float* noise,
+                 const float* noise_logits, hipStream_t s) {
   constexpr int EE = 8 * NEG;
   size_t lds = (size_t)2 * kKC * kXP * sizeof(double) + (size_t)2 * kKC * EE * sizeof(double) +
                (size_t)kTile * (c.n_experts + 1) * sizeof(float) + (size_t)c.top_k * c.n_experts * sizeof(int32_t);
@@ -381,13 +391,16 @@ void launch_gate(const moe_config_t& c, const RoutePlan& p, const void* x, const
   }
   hipLaunchKernelGGL((gate_topk_kernel<T, NEG>), dim3(p.nb), dim3(kGateThreads), lds, s, (const T*)x, wd, b_gate, logits,
                      probs, topk_idx, topk_w, hist, c.n_tokens, c.d_model, c.n_experts, c.top_k, c.renormalize, p.ep,
-                     p.nkc, p.nb);
+                     p.nkc, p.nb, noise, noise_logits);
 }
 
 template <typename T>
+// noise, noise_logits: NULL, or the inputs of the noisy gate (logits = x.W_g + b + noise * Softplus(noise_logits)).
+// gate_only: stop after the gate kernel (used to produce noise_logits = x.W_noise with the same kernel).
 moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
                      float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
-                     int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
+                     int32_t* offsets, int32_t* src_of_row, void* ws, const float* noise, const float* noise_logits,
+                     bool gate_only, hipStream_t s) {
   RoutePlan p = route_plan(c);
   unsigned char* w = static_cast<unsigned char*>(ws);
   double* wd = reinterpret_cast<double*>(w + p.off_wd);
@@ -398,12 +411,13 @@ moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, c
                      c.n_experts, p.mpad, p.ep);
   MOE_CHECK_LAUNCH();
   switch (p.ee) {
-    case 8: launch_gate<T, 1>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
-    case 16: launch_gate<T, 2>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
-    case 32: launch_gate<T, 4>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
-    default: launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, s); break;
+    case 8: launch_gate<T, 1>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, s); break;
+    case 16: launch_gate<T, 2>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, s); break;
+    case 32: launch_gate<T, 4>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, s); break;
+    default: launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, s); break;
   }
   MOE_CHECK_LAUNCH();
+  if (gate_only) return MOE_OK;
   hipLaunchKernelGGL(scan_hist_kernel, dim3(c.n_experts), dim3(256), 0, s, hist, total, c.top_k * p.nb);
   MOE_CHECK_LAUNCH();
   hipLaunchKernelGGL(positions_kernel, dim3(ceil_div(p.nb, 4)), dim3(256), 0, s, topk_idx, hist, total, count, offsets,
@@ -453,7 +467,8 @@ __global__ __launch_bounds__(256) void dlogits_kernel(const float* __restrict__ 
                                                       const int32_t* __restrict__ pos,
                                                       const float* __restrict__ dtopk_w, float* __restrict__ dl,
                                                       bf16_t* __restrict__ dlb, int n_tokens, int n_experts,
-                                                      int top_k, int ep, int gate) {
+                                                      int top_k, int ep, int gate, const float* __restrict__ noise,
+                                                      const float* __restrict__ noise_logits) {
   // one thread per (token, padded expert); dlb (optional) is the bf16 copy with zero columns up to ep
   const int width = dlb != nullptr ? ep : n_experts;
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -473,6 +488,10 @@ __global__ __launch_bounds__(256) void dlogits_kernel(const float* __restrict__ 
     }
     const float pe = probs[(size_t)t * n_experts + e];
     v = gate == MOE_GATE_SIGMOID ? g * pe * (1.0f - pe) : pe * (g - s);
+    if (noise != nullptr) {  // noisy gate: gradient of the I.W_noise product, dH * noise * sigma(I.W_noise)
+      const size_t gi = (size_t)t * n_experts + e;
+      v *= noise[gi] / (1.0f + expf(-noise_logits[gi]));
+    }
     dl[(size_t)t * n_experts + e] = v;
   }
   if (dlb != nullptr) dlb[i] = f32_to_bf16(v);
@@ -656,7 +675,8 @@ __global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __rest
 // fp32: plain FMA kernels.  dW_g through per-256-token partial sums reduced in tile order.
 moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                            const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
-                           float* db_gate, void* dx, void* ws, hipStream_t s) {
+                           float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
+                           hipStream_t s) {
   typedef float T;
   constexpr int V = Elem<T>::kVec;
   RouteBwdPlan p = route_bwd_plan(c);
@@ -666,7 +686,7 @@ moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_g
   float* bpart = reinterpret_cast<float*>(w + p.off_bpart);
   const size_t ne = (size_t)c.n_tokens * c.n_experts;
   hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
-                     dl, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0, c.renormalize);
+                     dl, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0, c.renormalize, noise, noise_logits);
   MOE_CHECK_LAUNCH();
   hipLaunchKernelGGL(gate_dx_kernel<T>, dim3(ceil_div(c.n_tokens, kDxTokens), ceil_div(c.d_model, 256 * V)), dim3(256),
                      (size_t)kDxTokens * c.n_experts * sizeof(float), s, dl, (const T*)w_gate, (T*)dx, c.n_tokens,
@@ -694,7 +714,8 @@ moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_g
 //   dW_g = x^T.dl    split-K groups of 512 tokens, bf16 partials summed in group order   (HBM-bound: x read)
 moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                             const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
-                            float* db_gate, void* dx, void* ws, hipStream_t s) {
+                            float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
+                            hipStream_t s) {
   RouteBwdPlan p = route_bwd_plan(c);
   unsigned char* w = static_cast<unsigned char*>(ws);
   float* dl = reinterpret_cast<float*>(w + p.off_dl);
@@ -705,7 +726,7 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
   int32_t* tok = reinterpret_cast<int32_t*>(w + p.off_tok);
   const size_t ne = (size_t)c.n_tokens * p.ep;
   hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
-                     dl, dlb, c.n_tokens, c.n_experts, c.top_k, p.ep, c.renormalize);
+                     dl, dlb, c.n_tokens, c.n_experts, c.top_k, p.ep, c.renormalize, noise, noise_logits);
   MOE_CHECK_LAUNCH();
   const int npad = c.d_model * p.ep > p.nsplit + 1 ? c.d_model * p.ep : p.nsplit + 1;
   hipLaunchKernelGGL(pad_gate_kernel, dim3(ceil_div(npad, 256)), dim3(256), 0, s, (const bf16_t*)w_gate, wgp, tok,
@@ -753,17 +774,49 @@ moe_status_t launch_route(const moe_config_t& c, const void* x, const void* w_ga
                           float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
                           int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
   return c.dtype == MOE_BF16 ? route_t<bf16_t>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
-                                               offsets, src_of_row, ws, s)
+                                               offsets, src_of_row, ws, nullptr, nullptr, false, s)
                              : route_t<float>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
-                                              offsets, src_of_row, ws, s);
+                                              offsets, src_of_row, ws, nullptr, nullptr, false, s);
+}
+
+// Noisy gate (Sec. 2.1): the gate kernel runs twice, first on W_noise (only its logits are kept: noise_logits),
+// then on W_g with the noise term added before the top-k.
+moe_status_t launch_route_noisy(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate,
+                                const void* w_noise, const float* noise, float* logits, float* noise_logits, float* probs,
+                                int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
+                                int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
+  const bool bf = c.dtype == MOE_BF16;
+  moe_status_t st = bf ? route_t<bf16_t>(c, x, w_noise, nullptr, noise_logits, probs, topk_idx, topk_w, pos, row_of, count,
+                                         offsets, src_of_row, ws, nullptr, nullptr, true, s)
+                       : route_t<float>(c, x, w_noise, nullptr, noise_logits, probs, topk_idx, topk_w, pos, row_of, count,
+                                        offsets, src_of_row, ws, nullptr, nullptr, true, s);
+  if (st != MOE_OK) return st;
+  return bf ? route_t<bf16_t>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count, offsets,
+                              src_of_row, ws, noise, noise_logits, false, s)
+            : route_t<float>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count, offsets,
+                             src_of_row, ws, noise, noise_logits, false, s);
 }
 
 moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                               const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                               float* db_gate, void* dx, void* ws, hipStream_t s) {
   return c.dtype == MOE_BF16
-             ? route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s)
-             : route_bwd_f32(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s);
+             ? route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, s)
+             : route_bwd_f32(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, s);
+}
+
+// Backward of the noisy gate: the ordinary gate backward for W_g (dH = dlogits), then the same products for
+// W_noise with dH * noise * sigma(noise_logits) in place of dH; both add their share to dx.
+moe_status_t launch_route_noisy_bwd(const moe_config_t& c, const void* x, const void* w_gate, const void* w_noise,
+                                    const float* noise, const float* noise_logits, const float* probs,
+                                    const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                                    float* db_gate, void* dw_noise, void* dx, void* ws, hipStream_t s) {
+  moe_status_t st = launch_route_bwd(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s);
+  if (st != MOE_OK) return st;
+  return c.dtype == MOE_BF16 ? route_bwd_bf16(c, x, w_noise, probs, topk_idx, pos, dtopk_w, dw_noise, nullptr, dx, ws,
+                                              noise, noise_logits, s)
+                             : route_bwd_f32(c, x, w_noise, probs, topk_idx, pos, dtopk_w, dw_noise, nullptr, dx, ws, noise,
+                                             noise_logits, s);
 }
 
 }  // namespace moe

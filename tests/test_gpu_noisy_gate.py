@@ -1,0 +1,62 @@
+"""The noisy gate of FSMoE Sec. 2.1 (noise draws passed in) through the C ABI against the oracle:
+routing bit-exact, logits bit-exact, gradients within the float tolerances."""
+import numpy as np
+import pytest
+import torch
+
+import moe_synth as S
+import paper_2501_10714_amd as moe
+from moe_harness import TOL, Buffers, assert_routing_equal, cap_of, make_cfg, rel_err, store, to_dev, to_np
+from oracle import moe_oracle as O
+
+pytestmark = pytest.mark.gpu
+W = S.WORKLOADS
+
+CASES = {
+    "noisy_bf16_topk": S.scaled(W["mixtral"], N=1000, M=256, H=64, E=8, k=2, seed=41),
+    "noisy_bf16_bias_drops": S.scaled(W["finegrained"], N=700, M=128, H=64, E=16, k=4, f=1.0, seed=42),
+    "noisy_f32_sigmoid": S.scaled(W["tiny"], N=333, M=72, H=64, E=5, k=2, f=1.2, renormalize=2, seed=43),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_noisy_route_forward_and_backward(name):
+    w = CASES[name]
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    x, wg, bg = S.draw_x(w), S.draw_w_gate(w), S.draw_b_gate(w)
+    wn, z, dtw = S.draw_w_noise(w), S.draw_noise(w), S.draw_dtopk_w(w)
+    f = lambda a: S.to_f64(a)
+    cap = cap_of(w)
+    ref = O.route_noisy(f(x), f(wg), None if bg is None else f(bg), f(wn), z.astype(np.float64), w.k, cap, w.renormalize)
+    nl = torch.empty(w.N, w.E, dtype=torch.float32, device="cuda")
+    moe.moe_route_noisy(cfg, to_dev(x), to_dev(wg), None if bg is None else to_dev(bg), to_dev(wn), to_dev(z), b.logits,
+                        nl, b.probs, b.topk_idx, b.topk_w, b.pos, b.row_of, b.count, b.offsets, b.src_of_row, b.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(nl.cpu().numpy(), ref["noise_logits"])
+    got_logits = b.logits.cpu().numpy()
+    assert np.array_equal(got_logits, ref["logits"]), f"{np.count_nonzero(got_logits != ref['logits'])} logits differ in bits"
+    assert_routing_equal({n: to_np(getattr(b, n)) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}, ref)
+    assert rel_err(to_np(b.probs), ref["probs"]) <= 1e-5
+    assert rel_err(to_np(b.topk_w), ref["topk_w"]) <= 1e-5
+    # the noise changes decisions: the same inputs without it route differently somewhere
+    plain = O.route(f(x), f(wg), None if bg is None else f(bg), w.k, cap, w.renormalize)
+    assert (plain["topk_idx"] != ref["topk_idx"]).any()
+
+    # backward from the oracle's forward tensors (rounded to what the call takes)
+    dl, dwg, dbg, dwn, dx = O.gate_bwd_noisy(f(x), f(wg), f(wn), z.astype(np.float64), ref["noise_logits"].astype(np.float64),
+                                             ref["logits"], ref["topk_idx"], ref["pos"], dtw.astype(np.float64),
+                                             w.renormalize, bg is not None)
+    base = store(0.25 * f(S.draw_dy(w)), w)      # something already in dx: the call accumulates
+    b.dx.copy_(to_dev(base))
+    dw_noise = torch.empty_like(b.dw_gate)
+    moe.moe_route_noisy_bwd(cfg, to_dev(x), to_dev(wg), to_dev(wn), to_dev(z), to_dev(ref["noise_logits"]),
+                            to_dev(ref["probs"].astype(np.float32)), to_dev(ref["topk_idx"]), to_dev(ref["pos"]), to_dev(dtw),
+                            b.dw_gate, b.db_gate if bg is not None else None, dw_noise, b.dx, b.ws)
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    assert rel_err(to_np(b.dw_gate), dwg) <= tol
+    assert rel_err(to_np(dw_noise), dwn) <= tol
+    assert rel_err(to_np(b.dx), S.to_f64(base) + dx) <= tol
+    if bg is not None:
+        assert rel_err(to_np(b.db_gate), dbg) <= 1e-4

@@ -479,3 +479,57 @@ def test_sigmoid_gate_values():
     l2 = logits.copy(); l2[0, 1] += 1.0
     w2 = O.gate_weights(l2, O.keep_top_k(l2, 2), O.GATE_SIGMOID)
     assert w2[0, 0] == w[0, 0] and w2[0, 1] > w[0, 1]
+
+
+# ----------------------------------------------------------------------------- noisy gate (Sec. 2.1)
+
+def test_softplus_values():
+    z = np.array([0.0, math.log(math.e - 1.0), -800.0, 800.0, -1.0])
+    want = [math.log(2.0), 1.0, 0.0, 800.0, math.log1p(math.exp(-1.0))]
+    np.testing.assert_allclose(O.softplus(z), want, rtol=1e-15, atol=1e-300)
+
+
+def test_noisy_logits_special_cases():
+    """Zero noise gives the plain gate; with W_noise = 0 every Softplus is ln 2, so H = I.W_g + ln2 * noise."""
+    g = rng(300)
+    x = g.standard_normal((9, 5)); wg = g.standard_normal((5, 4)); wn = g.standard_normal((5, 4)); bg = g.standard_normal(4)
+    z = g.standard_normal((9, 4))
+    h0, nl = O.gate_logits_noisy(x, wg, bg, wn, np.zeros((9, 4)), np.float64)
+    assert np.array_equal(h0, O.gate_logits(x, wg, bg, np.float64))
+    np.testing.assert_allclose(nl, x @ wn, rtol=1e-14)
+    h1, _ = O.gate_logits_noisy(x, wg, bg, np.zeros((5, 4)), z, np.float64)
+    np.testing.assert_allclose(h1, x @ wg + bg + math.log(2.0) * z, rtol=1e-14)
+    # one entry by hand
+    h2, _ = O.gate_logits_noisy(x, wg, None, wn, z, np.float64)
+    t, e = 3, 2
+    want = sum(x[t, m] * wg[m, e] for m in range(5)) + z[t, e] * math.log1p(math.exp(sum(x[t, m] * wn[m, e] for m in range(5))))
+    assert h2[t, e] == pytest.approx(want, rel=1e-13)
+
+
+@pytest.mark.parametrize("renorm,k,cap", [(1, 2, 0), (0, 3, 6), (O.GATE_SIGMOID, 2, 0)])
+def test_noisy_gate_backward_matches_central_differences(renorm, k, cap):
+    """L = sum_{kept (t,j)} c[t,j] * gate weight: its gradient with respect to W_g, b_g, W_noise and x, noise draws
+    and routing held fixed, against central differences."""
+    g = rng(310 + k)
+    n, m, e = 12, 5, 6
+    x = g.standard_normal((n, m)); wg = g.standard_normal((m, e)); wn = 0.5 * g.standard_normal((m, e))
+    bg = g.standard_normal(e); z = g.standard_normal((n, e)); c = g.standard_normal((n, k))
+    r0 = O.route_noisy(x, wg, bg, wn, z, k, cap, renorm, np.float64)
+
+    def loss(x_, wg_, bg_, wn_):
+        lg, _ = O.gate_logits_noisy(x_, wg_, bg_, wn_, z, np.float64)
+        w = O.gate_weights(lg, r0["topk_idx"], renorm)       # the decision of the unperturbed point
+        return float((c * w * (r0["pos"] >= 0)).sum())
+
+    dl, dwg, dbg, dwn, dx = O.gate_bwd_noisy(x, wg, wn, z, r0["noise_logits"], r0["logits"], r0["topk_idx"], r0["pos"], c,
+                                             renorm, True)
+    eps = 1e-6
+    for arr, grad, which in ((x, dx, 0), (wg, dwg, 1), (bg, dbg, 2), (wn, dwn, 3)):
+        flat = arr.reshape(-1)
+        for i in g.choice(flat.size, size=min(flat.size, 20), replace=False):
+            args = [x.copy(), wg.copy(), bg.copy(), wn.copy()]
+            args[which].reshape(-1)[i] += eps
+            up = loss(*args)
+            args[which].reshape(-1)[i] -= 2 * eps
+            dn = loss(*args)
+            assert grad.reshape(-1)[i] == pytest.approx((up - dn) / (2 * eps), rel=2e-5, abs=2e-8)
