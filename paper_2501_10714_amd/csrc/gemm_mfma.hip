@@ -499,27 +499,12 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   bf16x8 ax[4], bx[4], ay[4], by[4];  // fragment sets X (first 16 k of a stage) and Y (second 16 k)
-  auto load_frags = [&](bf16x8(&af)[4], bf16x8(&bf)[4], const unsigned char* a, const unsigned char* b, int s) {
-#pragma unroll
-    for (int f = 0; f < 4; ++f) af[f] = read_frag<LA>(a, wm * 128 + f * 32, s, lane);
-#pragma unroll
-    for (int f = 0; f < 4; ++f) bf[f] = read_frag<LB>(b, wn * 128 + f * 32, s, lane);
-  };
   auto mfma_step = [&](const bf16x8(&af)[4], const bf16x8(&bf)[4]) {
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
       for (int fn = 0; fn < 4; ++fn)
         acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[fn], af[fm], acc[fm][fn], 0, 0, 0);
-  };
-  constexpr int kReads = (LA == KC ? 4 : 8) + (LB == KC ? 4 : 8);  // LDS reads per k-step
-  auto interleave = [&]() {  // the k-step's LDS reads go out under the first MFMAs, so they are back at the barrier
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, (kReads + 3) / 4, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 12, 0);
   };
 
   int it_cur = 0;
@@ -541,10 +526,9 @@ __global__ __launch_bounds__(kThreads, 1) void gg_mfma_kernel(GemmP p, int n_nt,
       }
       ++it_cur;
     }
-    // Eight regions of 4 MFMAs, each with one load of stage S+3 and two fragment reads, interleaved
-    // by hand (the loads are assembly statements and the scheduler keeps everything else on its side
-    // of them).  The texture path takes ~16 cycles per load and four waves share it, so the loads are
-    // spread over the whole stage instead of being bunched behind the barrier.
+    // Eight groups of 4 MFMAs, each with one load of stage S+3 and two fragment reads.  The address unit
+    // of the CU takes ~16 cycles per load and four waves share it, so the loads are spread over the
+    // whole stage instead of being bunched behind the barrier.
     // First half: this stage's first fragments (X) under the MFMAs of the previous stage's second half (Y).
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

@@ -297,7 +297,7 @@ __global__ __launch_bounds__(256) void scan_hist_kernel(int32_t* __restrict__ hi
   part[threadIdx.x] = s;
   __syncthreads();
   for (int o = 1; o < 256; o <<= 1) {  // Hillis-Steele inclusive scan
-    int32_t v = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+    int32_t v = (int)threadIdx.x >= o ? part[threadIdx.x - o] : 0;
     __syncthreads();
     part[threadIdx.x] += v;
     __syncthreads();
@@ -511,10 +511,8 @@ __global__ void pad_gate_kernel(const bf16_t* __restrict__ w_gate, bf16_t* __res
 }
 
 __global__ __launch_bounds__(256) void gate_dw_reduce_bf16_kernel(const bf16_t* __restrict__ part,
-                                                                  const float* __restrict__ bpart,
-                                                                  bf16_t* __restrict__ dw_gate,
-                                                                  float* __restrict__ db_gate, int nsplit, int ntile,
-                                                                  int d_model, int n_experts, int ep) {
+                                                                  bf16_t* __restrict__ dw_gate, int nsplit, int d_model,
+                                                                  int n_experts, int ep) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < d_model * n_experts) {
     const int m = i / n_experts, e = i % n_experts;
@@ -659,10 +657,8 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __restrict__ part,
-                                                             const float* __restrict__ bpart, T* __restrict__ dw_gate,
-                                                             float* __restrict__ db_gate, int ntile, int d_model,
-                                                             int n_experts) {
+__global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __restrict__ part, T* __restrict__ dw_gate,
+                                                             int ntile, int d_model, int n_experts) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   const int n = d_model * n_experts;
   if (i < n) {
@@ -702,8 +698,8 @@ moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_g
     hipLaunchKernelGGL(colsum_final_kernel, dim3(c.n_experts), dim3(256), 0, s, bpart, db_gate, p.ntile, c.n_experts);
     MOE_CHECK_LAUNCH();
   }
-  hipLaunchKernelGGL(gate_dw_reduce_kernel<T>, dim3(ceil_div(c.d_model * c.n_experts, 256)), dim3(256), 0, s, part, bpart,
-                     (T*)dw_gate, db_gate, p.ntile, c.d_model, c.n_experts);
+  hipLaunchKernelGGL(gate_dw_reduce_kernel<T>, dim3(ceil_div(c.d_model * c.n_experts, 256)), dim3(256), 0, s, part,
+                     (T*)dw_gate, p.ntile, c.d_model, c.n_experts);
   MOE_CHECK_LAUNCH();
   return MOE_OK;
 }
@@ -760,7 +756,7 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
     MOE_CHECK_LAUNCH();
   }
   hipLaunchKernelGGL(gate_dw_reduce_bf16_kernel, dim3(ceil_div(c.d_model * c.n_experts, 256)), dim3(256), 0, s, part,
-                     bpart, (bf16_t*)dw_gate, db_gate, p.nsplit, p.ntile, c.d_model, c.n_experts, p.ep);
+                     (bf16_t*)dw_gate, p.nsplit, c.d_model, c.n_experts, p.ep);
   MOE_CHECK_LAUNCH();
   return MOE_OK;
 }
