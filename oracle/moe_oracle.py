@@ -24,13 +24,23 @@ What the paper defines and where (FSMoE, Sec. 2.1 unless noted):
   * backward:  every operation stores its activation and its gradient is computed
                by hand (Sec. 4.4); expert backward is twice the forward work
                                                          -> *_bwd
+  * other gates of Sec. 2.1: the sigmoid gate (expert output scaled by sigma(H_i))
+               -> gate_weights / gate_dense / gate_bwd with renormalize = 2;
+               the noise term of H(I), with the normal draws as an argument
+               -> gate_logits_noisy, route_noisy, gate_bwd_noisy
+  * chunks:    Sec. 4.2 cuts the capacity dimension into r parts that pass
+               through ordering and experts one after the other
+                                                         -> chunk_bounds, layer_fwd_chunked
 
 Readings taken where the paper is silent (each is listed in the design notes):
   ties in top-k go to the lower expert index; T is rounded up; when an expert
   overflows, all first choices are served before any second choice and earlier
   tokens first; gate weights are not renormalised after a drop; a token whose
   every choice is dropped outputs zero (plus the residual when requested);
-  experts have no biases; GELU is the tanh form unless the erf form is asked for.
+  experts have no biases; GELU is the tanh form unless the erf form is asked for;
+  the sigmoid gate keeps the top-k selection on the logits; the two products of the
+  noisy gate are each rounded to fp32 before H is formed from them in fp64; chunk c
+  of r of an expert with n rows is rows floor(c n / r) .. floor((c+1) n / r) - 1.
 
 Parity status: every function here is pinned by tests/test_oracle_pins.py
 (brute force on tiny inputs, closed forms, the dense one-hot formulation of the
