@@ -27,7 +27,9 @@ What the paper defines and where (FSMoE, Sec. 2.1 unless noted):
   * other gates of Sec. 2.1: the sigmoid gate (expert output scaled by sigma(H_i))
                -> gate_weights / gate_dense / gate_bwd with renormalize = 2;
                the noise term of H(I), with the normal draws as an argument
-               -> gate_logits_noisy, route_noisy, gate_bwd_noisy
+               -> gate_logits_noisy, route_noisy, gate_bwd_noisy;
+               the X-MoE scores s_i = cos(W_proj I, W_g[:, i]) after a low-rank projection
+               -> gate_logits_xmoe, route_xmoe, gate_bwd_xmoe
   * chunks:    Sec. 4.2 cuts the capacity dimension into r parts that pass
                through ordering and experts one after the other
                                                          -> chunk_bounds, layer_fwd_chunked
@@ -40,7 +42,9 @@ Readings taken where the paper is silent (each is listed in the design notes):
   experts have no biases; GELU is the tanh form unless the erf form is asked for;
   the sigmoid gate keeps the top-k selection on the logits; the two products of the
   noisy gate are each rounded to fp32 before H is formed from them in fp64; chunk c
-  of r of an expert with n rows is rows floor(c n / r) .. floor((c+1) n / r) - 1.
+  of r of an expert with n rows is rows floor(c n / r) .. floor((c+1) n / r) - 1;
+  the X-MoE projection is stored [M,D] and rounded to fp32 before the cosine is formed
+  in fp64, with no temperature and no epsilon.
 
 Parity status: every function here is pinned by tests/test_oracle_pins.py
 (brute force on tiny inputs, closed forms, the dense one-hot formulation of the
@@ -396,6 +400,55 @@ def gate_bwd_noisy(x, w_gate, w_noise, noise, noise_logits, logits, topk_idx, po
     dl, dw_gate, db_gate, dx = gate_bwd(x, w_gate, logits, topk_idx, pos, dtopk_w, renormalize, has_bias)
     dn = dl * np.asarray(noise, np.float64) * sigmoid(noise_logits)
     return dl, dw_gate, db_gate, x.T @ dn, dx + dn @ w_noise.T
+
+
+# ----------------------------------------------------------------------------- X-MoE gate (Sec. 2.1)
+
+def unit_rows(v, axis):
+    """v scaled to unit l2 length along `axis` (no epsilon: a zero vector has no direction and gives nan)."""
+    v = np.asarray(v, np.float64)
+    return v / np.sqrt((v * v).sum(axis=axis, keepdims=True))
+
+
+def gate_logits_xmoe(x, w_proj, w_gate, logit_dtype=np.float32):
+    """X-MoE routing scores of Sec. 2.1: the token is first projected to a low dimension D, projection and
+    expert embeddings are l2-normalised, and s_i = cos(W_proj I, W_g[:, i]).
+
+    Readings: w_proj is stored [M,D] and applied as I . W_proj (the same orientation as W_g [M,E] in H = I . W_g),
+    w_gate is [D,E] with one expert embedding per column; no temperature and no epsilon (the formula has none).
+    The projection is accumulated in fp64 and rounded once to fp32: it is an output, kept for the backward pass.
+    The cosine is then formed in fp64 from that fp32 tensor and rounded once to fp32, and the top-k is taken on
+    these scores.  Returns (s [N,E], projection [N,D])."""
+    proj = gate_logits(x, w_proj, None, logit_dtype)
+    s = unit_rows(proj, 1) @ unit_rows(w_gate, 0)
+    return s.astype(logit_dtype), proj
+
+
+def route_xmoe(x, w_proj, w_gate, k, cap, renormalize, logit_dtype=np.float32):
+    """route() with the X-MoE scores in place of I.W_g; everything after the scores is unchanged."""
+    logits, proj = gate_logits_xmoe(x, w_proj, w_gate, logit_dtype)
+    idx = keep_top_k(logits, k)
+    w = gate_weights(logits, idx, renormalize)
+    pos, count, offsets, row_of, src_of_row = assign_positions(idx, w_gate.shape[1], cap)
+    return dict(logits=logits, proj=proj, probs=gate_dense(logits, idx, renormalize), topk_idx=idx, topk_w=w,
+                pos=pos, count=count, offsets=offsets, row_of=row_of, src_of_row=src_of_row)
+
+
+def gate_bwd_xmoe(x, w_proj, w_gate, proj, logits, topk_idx, pos, dtopk_w, renormalize):
+    """Adjoint of the X-MoE gate with the routing decision held fixed.
+
+    ds as in gate_bwd.  s = pn . wn with pn = p / |p| (rows) and wn = w / |w| (columns), so the product gives
+    d(pn) = ds . wn^T and d(wn) = pn^T . ds, and a unit-length scaling u = v / |v| has the adjoint
+    dv = (du - u <u, du>) / |v|.  Then p = I . W_proj: dW_proj = x^T . dp, dx = dp . W_proj^T.
+    Returns ds [N,E], dW_proj [M,D], dW_g [D,E], and the gate's share of dx [N,M]."""
+    p = np.asarray(proj, np.float64)
+    wg = np.asarray(w_gate, np.float64)
+    pn, wn = unit_rows(p, 1), unit_rows(wg, 0)
+    ds, dwn, _, dpn = gate_bwd(pn, wn, logits, topk_idx, pos, dtopk_w, renormalize, False)
+    dp = (dpn - pn * (pn * dpn).sum(axis=1, keepdims=True)) / np.sqrt((p * p).sum(axis=1, keepdims=True))
+    dwg = (dwn - wn * (wn * dwn).sum(axis=0, keepdims=True)) / np.sqrt((wg * wg).sum(axis=0, keepdims=True))
+    x = np.asarray(x, np.float64)
+    return ds, x.T @ dp, dwg, dp @ np.asarray(w_proj, np.float64).T
 
 
 # ----------------------------------------------------------------------------- whole layer

@@ -533,3 +533,86 @@ def test_noisy_gate_backward_matches_central_differences(renorm, k, cap):
             args[which].reshape(-1)[i] -= 2 * eps
             dn = loss(*args)
             assert grad.reshape(-1)[i] == pytest.approx((up - dn) / (2 * eps), rel=2e-5, abs=2e-8)
+
+
+# ----------------------------------------------------------------------------- X-MoE gate (Sec. 2.1)
+
+def test_xmoe_scores_are_cosines():
+    """Hand values: cos((3,4),(4,3)) = 24/25, cos((1,0),(1,1)) = 1/sqrt 2, opposite vectors give -1, orthogonal 0;
+    every entry against the definition written with loops; and the invariances of a cosine."""
+    x = np.array([[3.0, 4.0], [1.0, 0.0], [-2.0, -2.0], [1.0, -1.0]])
+    wp = np.eye(2)
+    wg = np.array([[4.0, 1.0], [3.0, 1.0]])            # expert embeddings are the columns (4,3) and (1,1)
+    s, p = O.gate_logits_xmoe(x, wp, wg, np.float64)
+    assert np.array_equal(p, x)
+    want = np.array([[24 / 25, 7 / (5 * math.sqrt(2))], [4 / 5, 1 / math.sqrt(2)], [-7 / (5 * math.sqrt(2)), -1.0],
+                     [1 / (5 * math.sqrt(2)), 0.0]])
+    np.testing.assert_allclose(s, want, rtol=1e-14, atol=1e-16)
+
+    g = rng(400)
+    n, m, d, e = 7, 6, 3, 5
+    x = g.standard_normal((n, m)); wp = g.standard_normal((m, d)); wg = g.standard_normal((d, e))
+    s, p = O.gate_logits_xmoe(x, wp, wg, np.float64)
+    for t in range(n):
+        pr = [sum(x[t, i] * wp[i, j] for i in range(m)) for j in range(d)]
+        for i in range(e):
+            dot = sum(pr[j] * wg[j, i] for j in range(d))
+            na = math.sqrt(sum(v * v for v in pr)); nb = math.sqrt(sum(wg[j, i] ** 2 for j in range(d)))
+            assert s[t, i] == pytest.approx(dot / (na * nb), rel=1e-12, abs=1e-15)
+    assert np.all(np.abs(s) <= 1.0 + 1e-15)
+    # a cosine ignores the length of either vector: scaling tokens, the projection, or single embeddings
+    s2, _ = O.gate_logits_xmoe(x * g.uniform(0.5, 3.0, (n, 1)), 4.0 * wp, wg * g.uniform(0.5, 3.0, (1, e)), np.float64)
+    np.testing.assert_allclose(s2, s, rtol=1e-12, atol=1e-15)
+    # a rotation of the projected space applied to both sides leaves every score unchanged
+    rot, _ = np.linalg.qr(g.standard_normal((d, d)))
+    s3, _ = O.gate_logits_xmoe(x, wp @ rot, rot.T @ wg, np.float64)
+    np.testing.assert_allclose(s3, s, rtol=1e-12, atol=1e-14)
+    # unit tokens, identity projection, unit embeddings: the scores are the plain gate product
+    xu = x / np.linalg.norm(x, axis=1, keepdims=True); wu = g.standard_normal((m, e)); wu /= np.linalg.norm(wu, axis=0)
+    s4, _ = O.gate_logits_xmoe(xu, np.eye(m), wu, np.float64)
+    np.testing.assert_allclose(s4, O.gate_logits(xu, wu, None, np.float64), rtol=1e-12, atol=1e-15)
+
+
+def test_xmoe_route_is_route_on_the_scores():
+    """The decision and the layout come from the scores exactly as route() takes them from I.W_g: with unit tokens,
+    identity projection and unit embeddings the two routes agree in every integer output."""
+    g = rng(401)
+    n, m, e, k = 40, 8, 6, 2
+    x = g.standard_normal((n, m)); x /= np.linalg.norm(x, axis=1, keepdims=True)
+    wg = g.standard_normal((m, e)); wg /= np.linalg.norm(wg, axis=0)
+    a = O.route_xmoe(x, np.eye(m), wg, k, 9, 1, np.float64)
+    b = O.route(x, wg, None, k, 9, 1, np.float64)
+    for key in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row"):
+        assert np.array_equal(a[key], b[key]), key
+    np.testing.assert_allclose(a["topk_w"], b["topk_w"], rtol=1e-12)
+
+
+@pytest.mark.parametrize("renorm,k,cap", [(1, 2, 0), (0, 3, 7), (O.GATE_SIGMOID, 2, 0)])
+def test_xmoe_gate_backward_matches_central_differences(renorm, k, cap):
+    """L = sum_{kept (t,j)} c[t,j] * gate weight, as a function of x, W_proj and W_g with the routing held fixed."""
+    g = rng(410 + k)
+    n, m, d, e = 11, 6, 4, 5
+    x = g.standard_normal((n, m)); wp = g.standard_normal((m, d)); wg = g.standard_normal((d, e)); c = g.standard_normal((n, k))
+    r0 = O.route_xmoe(x, wp, wg, k, cap, renorm, np.float64)
+
+    def loss(x_, wp_, wg_):
+        s, _ = O.gate_logits_xmoe(x_, wp_, wg_, np.float64)
+        w = O.gate_weights(s, r0["topk_idx"], renorm)
+        return float((c * w * (r0["pos"] >= 0)).sum())
+
+    ds, dwp, dwg, dx = O.gate_bwd_xmoe(x, wp, wg, r0["proj"], r0["logits"], r0["topk_idx"], r0["pos"], c, renorm)
+    eps = 1e-6
+    for arr, grad, which in ((x, dx, 0), (wp, dwp, 1), (wg, dwg, 2)):
+        flat = arr.reshape(-1)
+        for i in g.choice(flat.size, size=min(flat.size, 20), replace=False):
+            args = [x.copy(), wp.copy(), wg.copy()]
+            args[which].reshape(-1)[i] += eps
+            up = loss(*args)
+            args[which].reshape(-1)[i] -= 2 * eps
+            dn = loss(*args)
+            assert grad.reshape(-1)[i] == pytest.approx((up - dn) / (2 * eps), rel=2e-5, abs=2e-8)
+    # the scores do not depend on the length of an embedding or of a projected token, so the gradient has no
+    # component along either: <dW_g[:,i], W_g[:,i]> = 0 and <dx[t], x[t]> = 0 (x scales its projection)
+    assert np.abs((dwg * wg).sum(axis=0)).max() < 1e-12
+    assert np.abs((dx * x).sum(axis=1)).max() < 1e-12
+    assert np.abs((dwp * wp).sum()) < 1e-12
