@@ -213,6 +213,33 @@ moe_status_t moe_route_noisy_bwd(const moe_config_t* cfg, const void* x, const v
                                  float* db_gate, void* dw_noise, void* dx, void* workspace, size_t workspace_bytes,
                                  void* stream);
 
+/* The X-MoE gate of Sec. 2.1: s_i = cos(W_proj I, W_g[:, i]).  The token is projected to d_proj dimensions,
+ * projection and expert embeddings are scaled to unit l2 length, and the cosine scores take the place of I.W_g
+ * in everything moe_route does (top-k, gate-weight function cfg->renormalize, capacity positions).
+ * The projection is accumulated in fp64 and rounded once to fp32; the scores are formed from it in fp64 and
+ * rounded once to fp32.  No temperature and no epsilon: a token whose projection is exactly zero gets NaN
+ * scores (its choices are then valid expert indices, but not meaningful).
+ * in : x [N,M] dtype; w_proj [M,d_proj] dtype (applied as x.W_proj); w_gate [d_proj,E] dtype, one expert
+ *      embedding per column; d_proj a multiple of 4, at most 256.
+ * out: proj [N,d_proj] f32 = x.W_proj (moe_route_xmoe_bwd needs it); logits [N,E] f32 = the scores; the rest
+ *      as moe_route.  All device pointers.
+ * workspace: moe_route_xmoe_workspace_bytes (device memory; MOE_ERR_WORKSPACE if smaller). */
+moe_status_t moe_route_xmoe_workspace_bytes(const moe_config_t* cfg, int32_t d_proj, size_t* ws_bytes);
+moe_status_t moe_route_xmoe(const moe_config_t* cfg, const void* x, const void* w_proj, const void* w_gate,
+                            int32_t d_proj, float* proj, float* logits, float* probs, int32_t* topk_idx, float* topk_w,
+                            int32_t* pos, int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of the X-MoE gate, routing decision held fixed.  With ds = dlogits as in moe_route_bwd, pn and wn
+ * the unit-length projection rows and embedding columns: d(pn) = ds.wn^T, d(wn) = pn^T.ds; a unit scaling
+ * u = v / |v| has the adjoint dv = (du - u <u, du>) / |v|; then dw_proj = x^T.dp and dx += dp.W_proj^T
+ * (ACCUMULATED INTO dx).  The two small steps run in fp64/fp32; the products with x as in moe_route_bwd.
+ * out: dw_proj [M,d_proj] dtype, dw_gate [d_proj,E] dtype. */
+moe_status_t moe_route_xmoe_bwd(const moe_config_t* cfg, const void* x, const void* w_proj, const void* w_gate,
+                                int32_t d_proj, const float* proj, const float* probs, const int32_t* topk_idx,
+                                const int32_t* pos, const float* dtopk_w, void* dw_proj, void* dw_gate, void* dx,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- pipeline degree (Sec. 4): host functions, no GPU work ------------------------------------------
  * Linear performance models of Sec. 4.1, Eq. (1): one of r chunks of AlltoAll (dispatch or combine),
  * ESP-AllGather, ESP-ReduceScatter and expert computation takes alpha + (n / r) * beta; n is the message

@@ -90,7 +90,7 @@ def to_f64(a: np.ndarray) -> np.ndarray:
 # ----------------------------------------------------------------------------- draws
 
 _TENSOR_IDS = {"x": 1, "w_gate": 2, "b_gate": 3, "w1": 4, "w3": 5, "w2": 6, "dy": 7, "perm": 8, "sample": 9,
-               "w_noise": 10, "noise": 11, "dtopk_w": 12}
+               "w_noise": 10, "noise": 11, "dtopk_w": 12, "w_proj": 13, "w_embed": 14}
 
 
 def _rng(seed: int, tensor: str, part: int = 0) -> np.random.Generator:
@@ -123,6 +123,16 @@ def draw_w_gate(w: Workload) -> np.ndarray:
 def draw_w_noise(w: Workload) -> np.ndarray:
     """W_noise of the noisy gate, like W_g."""
     return _store(_normal(w.seed, "w_noise", (w.M, w.E), 0.02), w.dtype)
+
+
+def draw_w_proj(w: Workload, d_proj: int) -> np.ndarray:
+    """W_proj of the X-MoE gate, [M, d_proj], initialised like W_g."""
+    return _store(_normal(w.seed, "w_proj", (w.M, d_proj), 0.02), w.dtype)
+
+
+def draw_w_embed(w: Workload, d_proj: int) -> np.ndarray:
+    """Expert embeddings of the X-MoE gate, [d_proj, E] (one per column)."""
+    return _store(_normal(w.seed, "w_embed", (d_proj, w.E), 0.5), w.dtype)
 
 
 def draw_noise(w: Workload) -> np.ndarray:

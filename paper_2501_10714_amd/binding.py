@@ -21,7 +21,8 @@ _LIB = None
 ENTRY_POINTS = ["moe_capacity", "moe_workspace_bytes", "moe_route", "moe_dispatch", "moe_dispatch_bwd",
                 "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_combine", "moe_combine_bwd", "moe_route_bwd",
                 "moe_layer_fwd", "moe_layer_bwd", "moe_layer_fwd_chunked", "moe_layer_bwd_chunked", "moe_saved_offset",
-                "moe_pipeline_time", "moe_find_pipeline_degree", "moe_route_noisy", "moe_route_noisy_bwd", "moe_last_error"]
+                "moe_pipeline_time", "moe_find_pipeline_degree", "moe_route_noisy", "moe_route_noisy_bwd", "moe_route_xmoe_workspace_bytes",
+                "moe_route_xmoe", "moe_route_xmoe_bwd", "moe_last_error"]
 MAX_CHUNKS = 16  # MOE_MAX_CHUNKS
 
 
@@ -205,3 +206,22 @@ def moe_route_noisy_bwd(cfg, x, w_gate, w_noise, noise, noise_logits, probs, top
     _check(load().moe_route_noisy_bwd(C.byref(cfg), _p(x), _p(w_gate), _p(w_noise), _p(noise), _p(noise_logits),
                                       _p(probs), _p(topk_idx), _p(pos), _p(dtopk_w), _p(dw_gate), _p(db_gate),
                                       _p(dw_noise), _p(dx), _p(ws), _sz(ws), _stream()))
+
+
+def moe_route_xmoe_workspace_bytes(cfg, d_proj) -> int:
+    ws = C.c_size_t(0)
+    _check(load().moe_route_xmoe_workspace_bytes(C.byref(cfg), C.c_int32(d_proj), C.byref(ws)))
+    return int(ws.value)
+
+
+def moe_route_xmoe(cfg, x, w_proj, w_gate, d_proj, proj, logits, probs, topk_idx, topk_w, pos, row_of, count, offsets,
+                   src_of_row, ws):
+    _check(load().moe_route_xmoe(C.byref(cfg), _p(x), _p(w_proj), _p(w_gate), C.c_int32(d_proj), _p(proj), _p(logits),
+                                 _p(probs), _p(topk_idx), _p(topk_w), _p(pos), _p(row_of), _p(count), _p(offsets),
+                                 _p(src_of_row), _p(ws), _sz(ws), _stream()))
+
+
+def moe_route_xmoe_bwd(cfg, x, w_proj, w_gate, d_proj, proj, probs, topk_idx, pos, dtopk_w, dw_proj, dw_gate, dx, ws):
+    _check(load().moe_route_xmoe_bwd(C.byref(cfg), _p(x), _p(w_proj), _p(w_gate), C.c_int32(d_proj), _p(proj), _p(probs),
+                                     _p(topk_idx), _p(pos), _p(dtopk_w), _p(dw_proj), _p(dw_gate), _p(dx), _p(ws),
+                                     _sz(ws), _stream()))

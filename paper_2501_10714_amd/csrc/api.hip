@@ -190,6 +190,51 @@ moe_status_t moe_route_noisy_bwd(const moe_config_t* cfg, const void* x, const v
                                 db_gate, dw_noise, dx, workspace, as_stream(stream));
 }
 
+static moe_status_t check_xmoe(const char* fn, const moe_config_t* cfg, int32_t d_proj, const void* workspace,
+                               size_t workspace_bytes_) {
+  REQUIRE(d_proj >= 4 && d_proj <= 256 && d_proj % 4 == 0, MOE_ERR_UNSUPPORTED,
+          "%s: d_proj=%d must be a multiple of 4 in 4..256", fn, d_proj);
+  REQUIRE(workspace != nullptr, MOE_ERR_INVALID_ARG, "%s: argument 'workspace' is NULL", fn);
+  const size_t need = route_xmoe_workspace_bytes(*cfg, d_proj);
+  REQUIRE(workspace_bytes_ >= need, MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes, need %zu", fn, workspace_bytes_, need);
+  return MOE_OK;
+}
+
+moe_status_t moe_route_xmoe_workspace_bytes(const moe_config_t* cfg, int32_t d_proj, size_t* ws_bytes) {
+  CHECK_CFG(cfg);
+  NOT_NULL(ws_bytes);
+  REQUIRE(d_proj >= 4 && d_proj <= 256 && d_proj % 4 == 0, MOE_ERR_UNSUPPORTED,
+          "moe_route_xmoe_workspace_bytes: d_proj=%d must be a multiple of 4 in 4..256", d_proj);
+  *ws_bytes = route_xmoe_workspace_bytes(*cfg, d_proj);
+  return MOE_OK;
+}
+
+moe_status_t moe_route_xmoe(const moe_config_t* cfg, const void* x, const void* w_proj, const void* w_gate,
+                            int32_t d_proj, float* proj, float* logits, float* probs, int32_t* topk_idx, float* topk_w,
+                            int32_t* pos, int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row,
+                            void* workspace, size_t workspace_bytes_, void* stream) {
+  CHECK_CFG(cfg);
+  NOT_NULL(x); NOT_NULL(w_proj); NOT_NULL(w_gate); NOT_NULL(proj); NOT_NULL(logits); NOT_NULL(probs); NOT_NULL(topk_idx);
+  NOT_NULL(topk_w); NOT_NULL(pos); NOT_NULL(row_of); NOT_NULL(count); NOT_NULL(offsets); NOT_NULL(src_of_row);
+  moe_status_t st = check_xmoe("moe_route_xmoe", cfg, d_proj, workspace, workspace_bytes_);
+  if (st != MOE_OK) return st;
+  return launch_route_xmoe(*cfg, x, w_proj, w_gate, d_proj, proj, logits, probs, topk_idx, topk_w, pos, row_of, count,
+                           offsets, src_of_row, workspace, as_stream(stream));
+}
+
+moe_status_t moe_route_xmoe_bwd(const moe_config_t* cfg, const void* x, const void* w_proj, const void* w_gate,
+                                int32_t d_proj, const float* proj, const float* probs, const int32_t* topk_idx,
+                                const int32_t* pos, const float* dtopk_w, void* dw_proj, void* dw_gate, void* dx,
+                                void* workspace, size_t workspace_bytes_, void* stream) {
+  CHECK_CFG(cfg);
+  NOT_NULL(x); NOT_NULL(w_proj); NOT_NULL(w_gate); NOT_NULL(proj); NOT_NULL(probs); NOT_NULL(topk_idx); NOT_NULL(pos);
+  NOT_NULL(dtopk_w); NOT_NULL(dw_proj); NOT_NULL(dw_gate); NOT_NULL(dx);
+  moe_status_t st = check_xmoe("moe_route_xmoe_bwd", cfg, d_proj, workspace, workspace_bytes_);
+  if (st != MOE_OK) return st;
+  return launch_route_xmoe_bwd(*cfg, x, w_proj, w_gate, d_proj, proj, probs, topk_idx, pos, dtopk_w, dw_proj, dw_gate, dx,
+                               workspace, as_stream(stream));
+}
+
 moe_status_t moe_dispatch(const moe_config_t* cfg, const void* x, const int32_t* row_of, void* xe, void* stream) {
   CHECK_CFG(cfg);
   NOT_NULL(x); NOT_NULL(row_of); NOT_NULL(xe);

@@ -120,6 +120,14 @@ moe_status_t launch_route_noisy_bwd(const moe_config_t& c, const void* x, const 
                                     const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                                     float* db_gate, void* dw_noise, void* dx, void* ws, hipStream_t s);
 size_t route_bwd_workspace_bytes(const moe_config_t& c);
+size_t route_xmoe_workspace_bytes(const moe_config_t& c, int d_proj);
+moe_status_t launch_route_xmoe(const moe_config_t& c, const void* x, const void* w_proj, const void* w_gate, int d_proj,
+                               float* proj, float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos,
+                               int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row, void* ws,
+                               hipStream_t s);
+moe_status_t launch_route_xmoe_bwd(const moe_config_t& c, const void* x, const void* w_proj, const void* w_gate, int d_proj,
+                                   const float* proj, const float* probs, const int32_t* topk_idx, const int32_t* pos,
+                                   const float* dtopk_w, void* dw_proj, void* dw_gate, void* dx, void* ws, hipStream_t s);
 moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                               const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                               float* db_gate, void* dx, void* ws, hipStream_t s);

@@ -26,6 +26,10 @@ constexpr int kKC = 64;            // k per staged chunk
 constexpr int kXP = kTile + 2;     // pitch (doubles) of a k-row of the staged x chunk
 constexpr int kMaxK = 8;
 
+// what gate_topk_kernel does: the whole gate; the product only (logits out, nothing else written); or top-k,
+// G(I) and the histogram on logits that are already there
+enum GateMode { kGateFull = 0, kGateLogitsOnly = 1, kGateFromLogits = 2 };
+
 struct RoutePlan {
   int ee;      // experts per pass (8,16,32,64)
   int ep;      // padded expert count (multiple of ee)
@@ -35,10 +39,20 @@ struct RoutePlan {
   size_t off_wd, off_hist, off_total, bytes;
 };
 
+// LDS of gate_topk_kernel with ee experts per pass: the two staged operands (double buffered), the tile's
+// logits, the histogram of choices
+size_t gate_lds_bytes(int ee, int n_experts, int top_k) {
+  return (size_t)2 * kKC * kXP * sizeof(double) + (size_t)2 * kKC * ee * sizeof(double) +
+         (size_t)kTile * (n_experts + 1) * sizeof(float) + (size_t)top_k * n_experts * sizeof(int32_t);
+}
+
 RoutePlan route_plan(const moe_config_t& c) {
   RoutePlan p;
   int e = c.n_experts;
   p.ee = e <= 8 ? 8 : e <= 16 ? 16 : e <= 32 ? 32 : 64;
+  // many experts: fewer per pass, so that the logits of the tile still fit beside the operands (160 KB of LDS;
+  // E = 256 with top_k = 8 fits at 16 per pass)
+  while (p.ee > 8 && gate_lds_bytes(p.ee, e, c.top_k) > (size_t)160 * 1024) p.ee /= 2;
   p.ep = ceil_div(e, p.ee) * p.ee;
   p.nkc = ceil_div(c.d_model, kKC);
   p.mpad = p.nkc * kKC;
@@ -92,7 +106,7 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
     const T* __restrict__ x, const double* __restrict__ wd, const float* __restrict__ b_gate,
     float* __restrict__ logits, float* __restrict__ probs, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     int32_t* __restrict__ hist, int n_tokens, int d_model, int n_experts, int top_k, int renormalize, int ep, int nkc,
-    int nb, const float* __restrict__ noise, const float* __restrict__ noise_logits) {
+    int nb, const float* __restrict__ noise, const float* __restrict__ noise_logits, int mode) {
   constexpr int EE = 8 * NEG;         // experts per pass
   constexpr int NKS = 32 / NEG;       // K slices
   constexpr int KPS = kKC / NKS;      // k per slice and chunk
@@ -117,7 +131,8 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
 
   for (int i = tid; i < top_k * n_experts; i += kGateThreads) hcnt[i] = 0;
 
-  for (int ec = 0; ec < ep; ec += EE) {
+  const int ep_run = mode == kGateFromLogits ? 0 : ep;
+  for (int ec = 0; ec < ep_run; ec += EE) {
     double acc[8][8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -226,10 +241,18 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
     __syncthreads();
   }
 
-  // logits out, coalesced over the tile
-  for (int i = tid; i < kTile * n_experts; i += kGateThreads) {
-    int tk = i / n_experts, e = i % n_experts;
-    if (t0 + tk < n_tokens) logits[(size_t)(t0 + tk) * n_experts + e] = lg[tk * lgs + e];
+  if (mode == kGateFromLogits) {  // the tile's logits come from memory
+    for (int i = tid; i < kTile * n_experts; i += kGateThreads) {
+      int tk = i / n_experts, e = i % n_experts;
+      lg[tk * lgs + e] = t0 + tk < n_tokens ? logits[(size_t)(t0 + tk) * n_experts + e] : 0.0f;
+    }
+    __syncthreads();
+  } else {  // logits out, coalesced over the tile
+    for (int i = tid; i < kTile * n_experts; i += kGateThreads) {
+      int tk = i / n_experts, e = i % n_experts;
+      if (t0 + tk < n_tokens) logits[(size_t)(t0 + tk) * n_experts + e] = lg[tk * lgs + e];
+    }
+    if (mode == kGateLogitsOnly) return;
   }
 
   // top-k and G(I): one token per lane of wave 0
@@ -248,6 +271,13 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
           float v = l[e];
           bool eligible = (j == 0) || (v < prev_v) || (v == prev_v && e > prev_e);
           if (eligible && (be < 0 || v > bv)) { bv = v; be = e; }
+        }
+        if (be < 0) {  // only with NaN logits (every comparison false): lowest expert not yet taken, so indices stay valid
+          for (int e = 0; e < n_experts && be < 0; ++e) {
+            bool taken = false;
+            for (int i = 0; i < j; ++i) taken |= sel[i] == e;
+            if (!taken) { be = e; bv = l[e]; }
+          }
         }
         sel[j] = be; selv[j] = bv; prev_v = bv; prev_e = be;
         topk_idx[(size_t)t * top_k + j] = be;
@@ -379,10 +409,9 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t* __restric
 template <typename T, int NEG>
 void launch_gate(const moe_config_t& c, const RoutePlan& p, const void* x, const double* wd, const float* b_gate,
                  float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* hist, const float* noise,
-                 const float* noise_logits, hipStream_t s) {
+                 const float* noise_logits, int mode, hipStream_t s) {
   constexpr int EE = 8 * NEG;
-  size_t lds = (size_t)2 * kKC * kXP * sizeof(double) + (size_t)2 * kKC * EE * sizeof(double) +
-               (size_t)kTile * (c.n_experts + 1) * sizeof(float) + (size_t)c.top_k * c.n_experts * sizeof(int32_t);
+  const size_t lds = gate_lds_bytes(EE, c.n_experts, c.top_k);
   static bool attr_set = false;  // LDS above 64 KB must be requested once per kernel
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gate_topk_kernel<T, NEG>),
@@ -391,33 +420,36 @@ void launch_gate(const moe_config_t& c, const RoutePlan& p, const void* x, const
   }
   hipLaunchKernelGGL((gate_topk_kernel<T, NEG>), dim3(p.nb), dim3(kGateThreads), lds, s, (const T*)x, wd, b_gate, logits,
                      probs, topk_idx, topk_w, hist, c.n_tokens, c.d_model, c.n_experts, c.top_k, c.renormalize, p.ep,
-                     p.nkc, p.nb, noise, noise_logits);
+                     p.nkc, p.nb, noise, noise_logits, mode);
 }
 
 template <typename T>
 // noise, noise_logits: NULL, or the inputs of the noisy gate (logits = x.W_g + b + noise * Softplus(noise_logits)).
-// gate_only: stop after the gate kernel (used to produce noise_logits = x.W_noise with the same kernel).
+// mode: kGateLogitsOnly stops after the product (logits out: noise_logits = x.W_noise, or the X-MoE projection);
+// kGateFromLogits takes `logits` as they are and does the rest (x, w_gate, b_gate are not read).
 moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
                      float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
                      int32_t* offsets, int32_t* src_of_row, void* ws, const float* noise, const float* noise_logits,
-                     bool gate_only, hipStream_t s) {
+                     int mode, hipStream_t s) {
   RoutePlan p = route_plan(c);
   unsigned char* w = static_cast<unsigned char*>(ws);
   double* wd = reinterpret_cast<double*>(w + p.off_wd);
   int32_t* hist = reinterpret_cast<int32_t*>(w + p.off_hist);
   int32_t* total = reinterpret_cast<int32_t*>(w + p.off_total);
   int nwd = p.mpad * p.ep;
-  hipLaunchKernelGGL(widen_gate_kernel<T>, dim3(ceil_div(nwd, 256)), dim3(256), 0, s, (const T*)w_gate, wd, c.d_model,
-                     c.n_experts, p.mpad, p.ep);
-  MOE_CHECK_LAUNCH();
+  if (mode != kGateFromLogits) {
+    hipLaunchKernelGGL(widen_gate_kernel<T>, dim3(ceil_div(nwd, 256)), dim3(256), 0, s, (const T*)w_gate, wd, c.d_model,
+                       c.n_experts, p.mpad, p.ep);
+    MOE_CHECK_LAUNCH();
+  }
   switch (p.ee) {
-    case 8: launch_gate<T, 1>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, s); break;
-    case 16: launch_gate<T, 2>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, s); break;
-    case 32: launch_gate<T, 4>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, s); break;
-    default: launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, s); break;
+    case 8: launch_gate<T, 1>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
+    case 16: launch_gate<T, 2>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
+    case 32: launch_gate<T, 4>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
+    default: launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
   }
   MOE_CHECK_LAUNCH();
-  if (gate_only) return MOE_OK;
+  if (mode == kGateLogitsOnly) return MOE_OK;
   hipLaunchKernelGGL(scan_hist_kernel, dim3(c.n_experts), dim3(256), 0, s, hist, total, c.top_k * p.nb);
   MOE_CHECK_LAUNCH();
   hipLaunchKernelGGL(positions_kernel, dim3(ceil_div(p.nb, 4)), dim3(256), 0, s, topk_idx, hist, total, count, offsets,
@@ -495,6 +527,15 @@ __global__ __launch_bounds__(256) void dlogits_kernel(const float* __restrict__ 
     dl[(size_t)t * n_experts + e] = v;
   }
   if (dlb != nullptr) dlb[i] = f32_to_bf16(v);
+}
+
+// bf16 copy of a gradient that is already there, with zero columns up to ep
+__global__ __launch_bounds__(256) void pad_dl_kernel(const float* __restrict__ dl, bf16_t* __restrict__ dlb,
+                                                     int n_tokens, int n_experts, int ep) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)n_tokens * ep) return;
+  const int t = (int)(i / ep), e = (int)(i % ep);
+  dlb[i] = f32_to_bf16(e < n_experts ? dl[(size_t)t * n_experts + e] : 0.0f);
 }
 
 // bf16 path helpers: W_g with zero columns up to ep, and the row ranges of the two grouped products
@@ -672,18 +713,22 @@ __global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __rest
 moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                            const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                            float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
-                           hipStream_t s) {
+                           const float* dl_ext, hipStream_t s) {
   typedef float T;
   constexpr int V = Elem<T>::kVec;
   RouteBwdPlan p = route_bwd_plan(c);
   unsigned char* w = static_cast<unsigned char*>(ws);
-  float* dl = reinterpret_cast<float*>(w + p.off_dl);
+  const float* dl = dl_ext;
   float* part = reinterpret_cast<float*>(w + p.off_part);
   float* bpart = reinterpret_cast<float*>(w + p.off_bpart);
-  const size_t ne = (size_t)c.n_tokens * c.n_experts;
-  hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
-                     dl, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0, c.renormalize, noise, noise_logits);
-  MOE_CHECK_LAUNCH();
+  if (dl_ext == nullptr) {
+    float* dl_own = reinterpret_cast<float*>(w + p.off_dl);
+    const size_t ne = (size_t)c.n_tokens * c.n_experts;
+    hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
+                       dl_own, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0, c.renormalize, noise, noise_logits);
+    MOE_CHECK_LAUNCH();
+    dl = dl_own;
+  }
   hipLaunchKernelGGL(gate_dx_kernel<T>, dim3(ceil_div(c.n_tokens, kDxTokens), ceil_div(c.d_model, 256 * V)), dim3(256),
                      (size_t)kDxTokens * c.n_experts * sizeof(float), s, dl, (const T*)w_gate, (T*)dx, c.n_tokens,
                      c.d_model, c.n_experts);
@@ -711,18 +756,25 @@ moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_g
 moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                             const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                             float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
-                            hipStream_t s) {
+                            const float* dl_ext, hipStream_t s) {
   RouteBwdPlan p = route_bwd_plan(c);
   unsigned char* w = static_cast<unsigned char*>(ws);
-  float* dl = reinterpret_cast<float*>(w + p.off_dl);
+  const float* dl = dl_ext;
   bf16_t* part = reinterpret_cast<bf16_t*>(w + p.off_part);
   float* bpart = reinterpret_cast<float*>(w + p.off_bpart);
   bf16_t* dlb = reinterpret_cast<bf16_t*>(w + p.off_dlb);
   bf16_t* wgp = reinterpret_cast<bf16_t*>(w + p.off_wgp);
   int32_t* tok = reinterpret_cast<int32_t*>(w + p.off_tok);
   const size_t ne = (size_t)c.n_tokens * p.ep;
-  hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
-                     dl, dlb, c.n_tokens, c.n_experts, c.top_k, p.ep, c.renormalize, noise, noise_logits);
+  if (dl_ext == nullptr) {
+    float* dl_own = reinterpret_cast<float*>(w + p.off_dl);
+    hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
+                       dl_own, dlb, c.n_tokens, c.n_experts, c.top_k, p.ep, c.renormalize, noise, noise_logits);
+    dl = dl_own;
+  } else {
+    hipLaunchKernelGGL(pad_dl_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, dl_ext, dlb, c.n_tokens,
+                       c.n_experts, p.ep);
+  }
   MOE_CHECK_LAUNCH();
   const int npad = c.d_model * p.ep > p.nsplit + 1 ? c.d_model * p.ep : p.nsplit + 1;
   hipLaunchKernelGGL(pad_gate_kernel, dim3(ceil_div(npad, 256)), dim3(256), 0, s, (const bf16_t*)w_gate, wgp, tok,
@@ -761,6 +813,193 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
   return MOE_OK;
 }
 
+// ----------------------------------------------------------------------------- X-MoE gate (Sec. 2.1)
+// s_i = cos(W_proj I, W_g[:, i]): the token is projected to D dimensions (the gate kernel with W_proj in the
+// place of W_g, logits only), projection and expert embeddings are scaled to unit length, and the scores
+// are their dot products, formed in fp64 and rounded once to fp32 like the logits of the plain gate.
+
+// wn[d][e] = W_g[d][e] / |W_g[:, e]| and col_norm[e] = |W_g[:, e]|, fp64; one thread per expert
+template <typename T>
+__global__ void xmoe_unit_columns_kernel(const T* __restrict__ w_gate, double* __restrict__ wn,
+                                         double* __restrict__ col_norm, int d_proj, int n_experts) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_experts) return;
+  double ss = 0.0;
+  for (int d = 0; d < d_proj; ++d) {
+    const double v = (double)Elem<T>::ld(w_gate + (size_t)d * n_experts + e);
+    ss = fma(v, v, ss);
+  }
+  const double nrm = sqrt(ss);
+  for (int d = 0; d < d_proj; ++d) wn[(size_t)d * n_experts + e] = (double)Elem<T>::ld(w_gate + (size_t)d * n_experts + e) / nrm;
+  col_norm[e] = nrm;
+}
+
+// scores[t][e] = fp32(<proj[t,:], wn[:,e]> / |proj[t,:]|); one thread per (token, expert)
+__global__ __launch_bounds__(256) void xmoe_scores_kernel(const float* __restrict__ proj, const double* __restrict__ wn,
+                                                          float* __restrict__ scores, int n_tokens, int d_proj,
+                                                          int n_experts) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)n_tokens * n_experts) return;
+  const int t = (int)(i / n_experts), e = (int)(i % n_experts);
+  const float* p = proj + (size_t)t * d_proj;
+  double ss = 0.0, dot = 0.0;
+  for (int d = 0; d < d_proj; ++d) {
+    const double v = (double)p[d];
+    ss = fma(v, v, ss);
+    dot = fma(v, wn[(size_t)d * n_experts + e], dot);
+  }
+  scores[i] = (float)(dot / sqrt(ss));
+}
+
+// Backward through the unit scaling of the projection, one thread per token:
+//   g[d] = sum_e ds[t,e] wn[d,e]   (gradient of the unit vector pn = p / |p|)
+//   dp   = (g - pn <pn, g>) / |p|
+// g is formed twice (once for <pn, g>, once for dp) instead of being kept.  pn is stored for the product
+// d(wn) = pn^T . ds.
+__global__ __launch_bounds__(256) void xmoe_bwd_token_kernel(const float* __restrict__ proj, const float* __restrict__ ds,
+                                                             const double* __restrict__ wn, float* __restrict__ dp,
+                                                             float* __restrict__ pn, int n_tokens, int d_proj,
+                                                             int n_experts) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= n_tokens) return;
+  const float* p = proj + (size_t)t * d_proj;
+  const float* g_in = ds + (size_t)t * n_experts;
+  double ss = 0.0, pg = 0.0;
+  for (int d = 0; d < d_proj; ++d) {
+    double g = 0.0;
+    for (int e = 0; e < n_experts; ++e) g = fma((double)g_in[e], wn[(size_t)d * n_experts + e], g);
+    const double v = (double)p[d];
+    ss = fma(v, v, ss);
+    pg = fma(v, g, pg);
+  }
+  const double inv = 1.0 / sqrt(ss);
+  const double c = pg * inv;  // <pn, g>
+  for (int d = 0; d < d_proj; ++d) {
+    double g = 0.0;
+    for (int e = 0; e < n_experts; ++e) g = fma((double)g_in[e], wn[(size_t)d * n_experts + e], g);
+    const double u = (double)p[d] * inv;
+    pn[(size_t)t * d_proj + d] = (float)u;
+    dp[(size_t)t * d_proj + d] = (float)((g - u * c) * inv);
+  }
+}
+
+// Backward through the unit scaling of the expert embeddings, one thread per expert:
+//   dW_g[:,e] = (dwn[:,e] - wn[:,e] <wn[:,e], dwn[:,e]>) / |W_g[:,e]|
+template <typename T>
+__global__ void xmoe_embed_grad_kernel(const float* __restrict__ dwn, const double* __restrict__ wn,
+                                       const double* __restrict__ col_norm, T* __restrict__ dw_gate, int d_proj,
+                                       int n_experts) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_experts) return;
+  double c = 0.0;
+  for (int d = 0; d < d_proj; ++d) c = fma(wn[(size_t)d * n_experts + e], (double)dwn[(size_t)d * n_experts + e], c);
+  const double inv = 1.0 / col_norm[e];
+  for (int d = 0; d < d_proj; ++d) {
+    const size_t i = (size_t)d * n_experts + e;
+    Elem<T>::st(dw_gate + i, (float)(((double)dwn[i] - wn[i] * c) * inv));
+  }
+}
+
+// the gate with D "experts": the projection I . W_proj and its backward are the plain gate product at that width
+moe_config_t proj_config(const moe_config_t& c, int d_proj) {
+  moe_config_t cd = c;
+  cd.n_experts = d_proj;
+  cd.top_k = 1;
+  return cd;
+}
+
+struct XmoePlan {
+  size_t off_wn, off_norm, off_ds, off_dp, off_pn, off_part, off_dwn, off_route, bytes;
+};
+
+XmoePlan xmoe_plan(const moe_config_t& c, int d_proj) {
+  XmoePlan p;
+  const moe_config_t cd = proj_config(c, d_proj);
+  const size_t N = c.n_tokens, E = c.n_experts, D = d_proj;
+  size_t o = 0;
+  p.off_wn = o; o += align_up(D * E * sizeof(double), 256);
+  p.off_norm = o; o += align_up(E * sizeof(double), 256);
+  // forward: the workspace of the gate kernel at width D, then at width E; backward: the buffers below
+  const size_t fwd = o + (route_plan(cd).bytes > route_plan(c).bytes ? route_plan(cd).bytes : route_plan(c).bytes);
+  p.off_ds = o; o += align_up(N * E * sizeof(float), 256);
+  p.off_dp = o; o += align_up(N * D * sizeof(float), 256);
+  p.off_pn = o; o += align_up(N * D * sizeof(float), 256);
+  p.off_part = o; o += align_up((size_t)ceil_div(c.n_tokens, kDwTokens) * D * E * sizeof(float), 256);
+  p.off_dwn = o; o += align_up(D * E * sizeof(float), 256);
+  p.off_route = o; o += route_bwd_plan(cd).bytes;
+  p.bytes = o > fwd ? o : fwd;
+  return p;
+}
+
+template <typename T>
+moe_status_t route_xmoe_t(const moe_config_t& c, const void* x, const void* w_proj, const void* w_gate, int d_proj,
+                          float* proj, float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos,
+                          int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
+  const XmoePlan p = xmoe_plan(c, d_proj);
+  unsigned char* w = static_cast<unsigned char*>(ws);
+  double* wn = reinterpret_cast<double*>(w + p.off_wn);
+  double* col_norm = reinterpret_cast<double*>(w + p.off_norm);
+  void* gate_ws = w + p.off_ds;  // the gate kernel's own workspace (shares the space of the backward buffers)
+  const moe_config_t cd = proj_config(c, d_proj);
+  moe_status_t st = route_t<T>(cd, x, w_proj, nullptr, proj, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                               nullptr, gate_ws, nullptr, nullptr, kGateLogitsOnly, s);
+  if (st != MOE_OK) return st;
+  hipLaunchKernelGGL(xmoe_unit_columns_kernel<T>, dim3(ceil_div(c.n_experts, 64)), dim3(64), 0, s, (const T*)w_gate, wn,
+                     col_norm, d_proj, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  const size_t ne = (size_t)c.n_tokens * c.n_experts;
+  hipLaunchKernelGGL(xmoe_scores_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, proj, wn, logits, c.n_tokens,
+                     d_proj, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  return route_t<T>(c, nullptr, nullptr, nullptr, logits, probs, topk_idx, topk_w, pos, row_of, count, offsets, src_of_row,
+                    gate_ws, nullptr, nullptr, kGateFromLogits, s);
+}
+
+template <typename T>
+moe_status_t route_xmoe_bwd_t(const moe_config_t& c, const void* x, const void* w_proj, const void* w_gate, int d_proj,
+                              const float* proj, const float* probs, const int32_t* topk_idx, const int32_t* pos,
+                              const float* dtopk_w, void* dw_proj, void* dw_gate, void* dx, void* ws, hipStream_t s) {
+  const XmoePlan p = xmoe_plan(c, d_proj);
+  unsigned char* w = static_cast<unsigned char*>(ws);
+  double* wn = reinterpret_cast<double*>(w + p.off_wn);
+  double* col_norm = reinterpret_cast<double*>(w + p.off_norm);
+  float* ds = reinterpret_cast<float*>(w + p.off_ds);
+  float* dp = reinterpret_cast<float*>(w + p.off_dp);
+  float* pn = reinterpret_cast<float*>(w + p.off_pn);
+  float* part = reinterpret_cast<float*>(w + p.off_part);
+  float* dwn = reinterpret_cast<float*>(w + p.off_dwn);
+  const int ntile = ceil_div(c.n_tokens, kDwTokens);
+  const size_t ne = (size_t)c.n_tokens * c.n_experts;
+  // ds: gradient of the scores (the softmax or sigmoid Jacobian on the kept choices)
+  hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
+                     ds, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0, c.renormalize, (const float*)nullptr,
+                     (const float*)nullptr);
+  MOE_CHECK_LAUNCH();
+  hipLaunchKernelGGL(xmoe_unit_columns_kernel<T>, dim3(ceil_div(c.n_experts, 64)), dim3(64), 0, s, (const T*)w_gate, wn,
+                     col_norm, d_proj, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  hipLaunchKernelGGL(xmoe_bwd_token_kernel, dim3(ceil_div(c.n_tokens, 256)), dim3(256), 0, s, proj, ds, wn, dp, pn,
+                     c.n_tokens, d_proj, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  // d(wn) = pn^T . ds through per-tile partial sums in fp32, reduced in tile order
+  hipLaunchKernelGGL(gate_dw_partial_kernel<float>, dim3(ntile, ceil_div(d_proj, kDwThreads * 4), ceil_div(c.n_experts, kEc)),
+                     dim3(kDwThreads), 0, s, (const float*)pn, (const float*)ds, part, c.n_tokens, d_proj, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  hipLaunchKernelGGL(gate_dw_reduce_kernel<float>, dim3(ceil_div(d_proj * c.n_experts, 256)), dim3(256), 0, s,
+                     (const float*)part, dwn, ntile, d_proj, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  hipLaunchKernelGGL(xmoe_embed_grad_kernel<T>, dim3(ceil_div(c.n_experts, 64)), dim3(64), 0, s, (const float*)dwn,
+                     (const double*)wn, (const double*)col_norm, (T*)dw_gate, d_proj, c.n_experts);
+  MOE_CHECK_LAUNCH();
+  // p = I . W_proj: dW_proj = x^T . dp and dx += dp . W_proj^T, the gate's products at width D
+  const moe_config_t cd = proj_config(c, d_proj);
+  if (c.dtype == MOE_BF16)
+    return route_bwd_bf16(cd, x, w_proj, nullptr, nullptr, nullptr, nullptr, dw_proj, nullptr, dx, w + p.off_route, nullptr,
+                          nullptr, dp, s);
+  return route_bwd_f32(cd, x, w_proj, nullptr, nullptr, nullptr, nullptr, dw_proj, nullptr, dx, w + p.off_route, nullptr,
+                       nullptr, dp, s);
+}
+
 }  // namespace
 
 size_t route_workspace_bytes(const moe_config_t& c) { return route_plan(c).bytes; }
@@ -770,9 +1009,9 @@ moe_status_t launch_route(const moe_config_t& c, const void* x, const void* w_ga
                           float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
                           int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
   return c.dtype == MOE_BF16 ? route_t<bf16_t>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
-                                               offsets, src_of_row, ws, nullptr, nullptr, false, s)
+                                               offsets, src_of_row, ws, nullptr, nullptr, kGateFull, s)
                              : route_t<float>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
-                                              offsets, src_of_row, ws, nullptr, nullptr, false, s);
+                                              offsets, src_of_row, ws, nullptr, nullptr, kGateFull, s);
 }
 
 // Noisy gate (Sec. 2.1): the gate kernel runs twice, first on W_noise (only its logits are kept: noise_logits),
@@ -783,22 +1022,22 @@ moe_status_t launch_route_noisy(const moe_config_t& c, const void* x, const void
                                 int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
   const bool bf = c.dtype == MOE_BF16;
   moe_status_t st = bf ? route_t<bf16_t>(c, x, w_noise, nullptr, noise_logits, probs, topk_idx, topk_w, pos, row_of, count,
-                                         offsets, src_of_row, ws, nullptr, nullptr, true, s)
+                                         offsets, src_of_row, ws, nullptr, nullptr, kGateLogitsOnly, s)
                        : route_t<float>(c, x, w_noise, nullptr, noise_logits, probs, topk_idx, topk_w, pos, row_of, count,
-                                        offsets, src_of_row, ws, nullptr, nullptr, true, s);
+                                        offsets, src_of_row, ws, nullptr, nullptr, kGateLogitsOnly, s);
   if (st != MOE_OK) return st;
   return bf ? route_t<bf16_t>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count, offsets,
-                              src_of_row, ws, noise, noise_logits, false, s)
+                              src_of_row, ws, noise, noise_logits, kGateFull, s)
             : route_t<float>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count, offsets,
-                             src_of_row, ws, noise, noise_logits, false, s);
+                             src_of_row, ws, noise, noise_logits, kGateFull, s);
 }
 
 moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                               const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                               float* db_gate, void* dx, void* ws, hipStream_t s) {
   return c.dtype == MOE_BF16
-             ? route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, s)
-             : route_bwd_f32(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, s);
+             ? route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, nullptr, s)
+             : route_bwd_f32(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, nullptr, s);
 }
 
 // Backward of the noisy gate: the ordinary gate backward for W_g (dH = dlogits), then the same products for
@@ -810,9 +1049,30 @@ moe_status_t launch_route_noisy_bwd(const moe_config_t& c, const void* x, const 
   moe_status_t st = launch_route_bwd(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s);
   if (st != MOE_OK) return st;
   return c.dtype == MOE_BF16 ? route_bwd_bf16(c, x, w_noise, probs, topk_idx, pos, dtopk_w, dw_noise, nullptr, dx, ws,
-                                              noise, noise_logits, s)
+                                              noise, noise_logits, nullptr, s)
                              : route_bwd_f32(c, x, w_noise, probs, topk_idx, pos, dtopk_w, dw_noise, nullptr, dx, ws, noise,
-                                             noise_logits, s);
+                                             noise_logits, nullptr, s);
+}
+
+size_t route_xmoe_workspace_bytes(const moe_config_t& c, int d_proj) { return xmoe_plan(c, d_proj).bytes; }
+
+moe_status_t launch_route_xmoe(const moe_config_t& c, const void* x, const void* w_proj, const void* w_gate, int d_proj,
+                               float* proj, float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos,
+                               int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row, void* ws,
+                               hipStream_t s) {
+  return c.dtype == MOE_BF16 ? route_xmoe_t<bf16_t>(c, x, w_proj, w_gate, d_proj, proj, logits, probs, topk_idx, topk_w, pos,
+                                                    row_of, count, offsets, src_of_row, ws, s)
+                             : route_xmoe_t<float>(c, x, w_proj, w_gate, d_proj, proj, logits, probs, topk_idx, topk_w, pos,
+                                                   row_of, count, offsets, src_of_row, ws, s);
+}
+
+moe_status_t launch_route_xmoe_bwd(const moe_config_t& c, const void* x, const void* w_proj, const void* w_gate, int d_proj,
+                                   const float* proj, const float* probs, const int32_t* topk_idx, const int32_t* pos,
+                                   const float* dtopk_w, void* dw_proj, void* dw_gate, void* dx, void* ws, hipStream_t s) {
+  return c.dtype == MOE_BF16 ? route_xmoe_bwd_t<bf16_t>(c, x, w_proj, w_gate, d_proj, proj, probs, topk_idx, pos, dtopk_w,
+                                                        dw_proj, dw_gate, dx, ws, s)
+                             : route_xmoe_bwd_t<float>(c, x, w_proj, w_gate, d_proj, proj, probs, topk_idx, pos, dtopk_w,
+                                                       dw_proj, dw_gate, dx, ws, s);
 }
 
 }  // namespace moe

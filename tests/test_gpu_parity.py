@@ -39,6 +39,9 @@ CASES = {
     # sigmoid gate (Sec. 2.1): weights sigma(H_i), no normalisation over the choices
     "sigmoid_glu": S.scaled(W["mixtral"], N=900, M=128, H=192, E=8, k=2, renormalize=2, seed=31),
     "sigmoid_f32_drops": S.scaled(W["tiny"], N=400, M=64, H=96, E=6, k=3, f=1.0, renormalize=2, seed=32),
+    # the largest expert count and top-k the library takes: the gate kernel then holds fewer experts per pass
+    "experts_256_bf16": S.scaled(W["finegrained"], N=300, M=64, H=64, E=256, k=8, seed=33),
+    "experts_130_f32": S.scaled(W["tiny"], N=200, M=40, H=64, E=130, k=8, f=1.5, seed=34),
 }
 
 
