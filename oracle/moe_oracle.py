@@ -29,7 +29,9 @@ What the paper defines and where (FSMoE, Sec. 2.1 unless noted):
                the noise term of H(I), with the normal draws as an argument
                -> gate_logits_noisy, route_noisy, gate_bwd_noisy;
                the X-MoE scores s_i = cos(W_proj I, W_g[:, i]) after a low-rank projection
-               -> gate_logits_xmoe, route_xmoe, gate_bwd_xmoe
+               -> gate_logits_xmoe, route_xmoe, gate_bwd_xmoe;
+               expert choice, G(I) = Softmax(KeepTopK((I.W_g)^T, k)): every expert keeps its top tokens
+               -> route_expert_choice, expert_choice_dense, gate_bwd with renormalize = 3
   * chunks:    Sec. 4.2 cuts the capacity dimension into r parts that pass
                through ordering and experts one after the other
                                                          -> chunk_bounds, layer_fwd_chunked
@@ -44,7 +46,9 @@ Readings taken where the paper is silent (each is listed in the design notes):
   noisy gate are each rounded to fp32 before H is formed from them in fp64; chunk c
   of r of an expert with n rows is rows floor(c n / r) .. floor((c+1) n / r) - 1;
   the X-MoE projection is stored [M,D] and rounded to fp32 before the cosine is formed
-  in fp64, with no temperature and no epsilon.
+  in fp64, with no temperature and no epsilon; expert choice: ties go to the earlier
+  token, an expert's rows are its kept tokens in token order, and the capacity argument
+  is the number of tokens every expert keeps.
 
 Parity status: every function here is pinned by tests/test_oracle_pins.py
 (brute force on tiny inputs, closed forms, the dense one-hot formulation of the
@@ -117,6 +121,7 @@ def softmax_all(logits):
 GATE_SOFTMAX_ALL = 0   # softmax over all E, the selected probabilities used as they are
 GATE_SOFTMAX_TOPK = 1  # Softmax(KeepTopK(H, k)) as printed in Sec. 2.1
 GATE_SIGMOID = 2       # the sigmoid gate of Sec. 2.1 (BASE, StableMoE): expert output scaled by sigma(H_i)
+GATE_EXPERT_CHOICE = 3  # expert choice (Sec. 2.1): every expert keeps its top tokens, Softmax(KeepTopK(H^T, k))
 
 
 def sigmoid(z):
@@ -363,6 +368,7 @@ def gate_bwd(x, w_gate, logits, topk_idx, pos, dtopk_w, renormalize, has_bias):
     renormalize=0: dl = p * (g - <g,p>), p the softmax over all E.
     renormalize=1: the same formula on the k selected entries with p -> w; other entries 0.
     renormalize=2 (sigmoid gate): dl = g * p * (1 - p), p = sigma(logits): the choices do not interact.
+    renormalize=3 (expert choice): slot j of a token is expert j; dl = p * (g - sum over tokens of g * p), column-wise.
     Returns dlogits [N,E], dW_g [M,E], db_g [E] or None, and the gate's share of dx [N,M]."""
     n, k = topk_idx.shape
     e_cnt = logits.shape[1]
@@ -371,11 +377,17 @@ def gate_bwd(x, w_gate, logits, topk_idx, pos, dtopk_w, renormalize, has_bias):
         for j in range(k):
             if pos[t, j] >= 0:
                 g[t, topk_idx[t, j]] = dtopk_w[t, j]
-    p = gate_dense(logits, topk_idx, renormalize)
-    if renormalize == GATE_SIGMOID:
-        dl = g * p * (1.0 - p)
+    if renormalize == GATE_EXPERT_CHOICE:
+        # the softmax runs over the tokens an expert kept (down a column), so the same Jacobian couples the
+        # kept tokens of one expert instead of the kept experts of one token
+        p = expert_choice_dense(logits, pos)
+        dl = p * (g - (g * p).sum(axis=0, keepdims=True))
     else:
-        dl = p * (g - (g * p).sum(axis=1, keepdims=True))
+        p = gate_dense(logits, topk_idx, renormalize)
+        if renormalize == GATE_SIGMOID:
+            dl = g * p * (1.0 - p)
+        else:
+            dl = p * (g - (g * p).sum(axis=1, keepdims=True))
     dw_gate = x.T @ dl
     db_gate = dl.sum(axis=0) if has_bias else None
     return dl, dw_gate, db_gate, dl @ w_gate.T
@@ -451,9 +463,59 @@ def gate_bwd_xmoe(x, w_proj, w_gate, proj, logits, topk_idx, pos, dtopk_w, renor
     return ds, x.T @ dp, dwg, dp @ np.asarray(w_proj, np.float64).T
 
 
+# ----------------------------------------------------------------------------- expert choice (Sec. 2.1)
+
+def expert_choice_dense(logits, pos):
+    """G^T as an [N,E] matrix for expert choice: down every column, the softmax over the tokens that expert
+    kept (pos >= 0), zeros elsewhere."""
+    l = np.asarray(logits, np.float64)
+    p = np.zeros(l.shape, np.float64)
+    for e in range(l.shape[1]):
+        kept = np.asarray(pos)[:, e] >= 0
+        if kept.any():
+            z = np.exp(l[kept, e] - l[kept, e].max())
+            p[kept, e] = z / z.sum()
+    return p
+
+
+def route_expert_choice(x, w_gate, b_gate, k_tokens, logit_dtype=np.float32):
+    """Expert choice: G(I) = Softmax(KeepTopK((I.W_g)^T, k)): the logits are transposed, so KeepTopK runs along
+    the tokens and every expert keeps its k_tokens largest (all N when k_tokens >= N); the softmax is over the
+    kept logits of that expert, as printed.  Ties go to the earlier token.
+
+    Layout, in the terms of the rest of the layer: a token has one slot per expert (topk_idx[t, j] = j), kept
+    or not (pos = -1, weight 0); the rows of an expert are its kept tokens in token order."""
+    logits = gate_logits(x, w_gate, b_gate, logit_dtype)
+    n, e_cnt = logits.shape
+    k = min(int(k_tokens), n)
+    assert k >= 1
+    kept = keep_top_k(logits.T, k)                 # [E,k] token indices, largest logit first
+    w_kept = gate_weights(logits.T, kept, 1)       # Softmax over the kept logits of every expert
+    pos = np.full((n, e_cnt), -1, np.int32)
+    w = np.zeros((n, e_cnt), np.float64)
+    for e in range(e_cnt):
+        for p_, t in enumerate(sorted(int(t) for t in kept[e])):
+            pos[t, e] = p_
+        w[kept[e].astype(np.int64), e] = w_kept[e]
+    count = np.full(e_cnt, k, np.int32)
+    offsets = (np.arange(e_cnt + 1) * k).astype(np.int32)
+    row_of = np.where(pos >= 0, offsets[None, :-1] + pos, -1).astype(np.int32)
+    src_of_row = np.full(n * e_cnt, -1, np.int32)
+    for t in range(n):
+        for e in range(e_cnt):
+            if row_of[t, e] >= 0:
+                src_of_row[row_of[t, e]] = t * e_cnt + e
+    topk_idx = np.tile(np.arange(e_cnt, dtype=np.int32), (n, 1))
+    return dict(logits=logits, probs=w.copy(), topk_idx=topk_idx, topk_w=w, pos=pos, count=count, offsets=offsets,
+                row_of=row_of, src_of_row=src_of_row)
+
+
 # ----------------------------------------------------------------------------- whole layer
 
 def route(x, w_gate, b_gate, k, cap, renormalize, logit_dtype=np.float32):
+    if renormalize == GATE_EXPERT_CHOICE:
+        assert k == w_gate.shape[1], "expert choice: a token has one slot per expert"
+        return route_expert_choice(x, w_gate, b_gate, cap, logit_dtype)
     logits = gate_logits(x, w_gate, b_gate, logit_dtype)
     idx = keep_top_k(logits, k)
     w = gate_weights(logits, idx, renormalize)

@@ -340,7 +340,8 @@ def _loss_and_grads(params, dy, k, cap, act, renorm, resid):
 @pytest.mark.parametrize("act,k,cap,renorm,resid", [
     (O.ACT_RELU, 1, 5, 0, 0), (O.ACT_GELU_TANH, 2, 7, 0, 1), (O.ACT_SWIGLU, 2, 0, 1, 0),
     (O.ACT_SWIGLU, 3, 8, 0, 0), (O.ACT_GELU_ERF, 2, 0, 1, 1), (O.ACT_GELU_TANH, 1, 0, 1, 0),
-    (O.ACT_SWIGLU, 2, 0, O.GATE_SIGMOID, 0), (O.ACT_GELU_TANH, 3, 6, O.GATE_SIGMOID, 1)])
+    (O.ACT_SWIGLU, 2, 0, O.GATE_SIGMOID, 0), (O.ACT_GELU_TANH, 3, 6, O.GATE_SIGMOID, 1),
+    (O.ACT_SWIGLU, 4, 5, O.GATE_EXPERT_CHOICE, 0), (O.ACT_GELU_TANH, 4, 9, O.GATE_EXPERT_CHOICE, 1)])
 def test_layer_backward_matches_central_differences(act, k, cap, renorm, resid):
     r = rng(70 + act + 10 * k)
     n, m, h, e = 14, 4, 5, 4
@@ -368,6 +369,7 @@ def test_layer_backward_matches_central_differences(act, k, cap, renorm, resid):
             fm = O.layer_fwd(*params, k, cap, act, renorm, resid, logit_dtype=np.float64)
             flat[i] = old
             assert np.array_equal(fp["topk_idx"], fwd["topk_idx"]) and np.array_equal(fm["topk_idx"], fwd["topk_idx"])
+            assert np.array_equal(fp["pos"], fwd["pos"]) and np.array_equal(fm["pos"], fwd["pos"])
             fd = float(((fp["y"] - fm["y"]) * dy).sum() / (2 * eps))
             an = float(g[name].reshape(-1)[i])
             assert abs(fd - an) <= 2e-6 * max(1.0, abs(an)), (name, i, fd, an)
@@ -616,3 +618,81 @@ def test_xmoe_gate_backward_matches_central_differences(renorm, k, cap):
     assert np.abs((dwg * wg).sum(axis=0)).max() < 1e-12
     assert np.abs((dx * x).sum(axis=1)).max() < 1e-12
     assert np.abs((dwp * wp).sum()) < 1e-12
+
+
+# ----------------------------------------------------------------------------- expert choice (Sec. 2.1)
+
+@pytest.mark.parametrize("n,e,k", [(17, 3, 5), (12, 4, 1), (9, 2, 9), (7, 3, 20)])
+def test_expert_choice_matches_sorted_columns_and_the_printed_formula(n, e, k):
+    g = rng(500 + n)
+    x = g.standard_normal((n, 6)); wg = g.standard_normal((6, e)); bg = g.standard_normal(e)
+    r = O.route_expert_choice(x, wg, bg, k, np.float64)
+    h = x @ wg + bg
+    kk = min(k, n)
+    for i in range(e):
+        # brute force: sort the tokens of the column by (logit descending, token ascending), keep the first k
+        want = sorted(sorted(range(n), key=lambda t: (-h[t, i], t))[:kk])
+        got = [t for t in range(n) if r["pos"][t, i] >= 0]
+        assert got == want
+        assert [int(r["pos"][t, i]) for t in got] == list(range(kk))       # rows in token order
+        # Softmax(KeepTopK(H^T, k)) spelled out: -inf outside the kept entries of the expert's row of H^T
+        row = np.full(n, -np.inf); row[want] = h[want, i]
+        z = np.exp(row - row.max()); lit = z / z.sum()
+        np.testing.assert_allclose(r["topk_w"][:, i], lit, rtol=1e-13, atol=0)
+        assert r["topk_w"][:, i].sum() == pytest.approx(1.0, abs=1e-14)
+    assert np.array_equal(r["count"], np.full(e, kk)) and np.array_equal(r["offsets"], np.arange(e + 1) * kk)
+    assert np.array_equal(r["topk_idx"], np.tile(np.arange(e), (n, 1)))
+    assert np.array_equal(r["probs"], r["topk_w"])
+    np.testing.assert_allclose(O.expert_choice_dense(h, r["pos"]), r["probs"], rtol=1e-13, atol=0)
+    # the two index maps are inverse to each other and cover exactly the rows 0 .. E k - 1
+    rows = r["row_of"][r["row_of"] >= 0]
+    assert sorted(rows.tolist()) == list(range(e * kk))
+    for t in range(n):
+        for i in range(e):
+            if r["row_of"][t, i] >= 0:
+                assert r["src_of_row"][r["row_of"][t, i]] == t * e + i
+                assert r["row_of"][t, i] == r["offsets"][i] + r["pos"][t, i]
+    assert np.all(r["src_of_row"][e * kk:] == -1)
+
+
+def test_expert_choice_tie_goes_to_the_earlier_token():
+    x = np.array([[1.0], [2.0], [2.0], [0.5], [2.0]])
+    r = O.route_expert_choice(x, np.array([[1.0, -1.0]]), None, 2, np.float64)
+    assert [t for t in range(5) if r["pos"][t, 0] >= 0] == [1, 2]           # three equal maxima: the first two
+    assert [t for t in range(5) if r["pos"][t, 1] >= 0] == [0, 3]           # column of -x: the two smallest x
+    np.testing.assert_allclose(r["topk_w"][[1, 2], 0], [0.5, 0.5])
+
+
+def test_expert_choice_with_every_token_kept_is_a_dense_mixture():
+    """k >= N: every expert processes every token, weighted by the softmax over the tokens of its column; with
+    identical experts the layer is (sum of the token's weights) * FFN(token)."""
+    g = rng(510)
+    n, m, h, e = 6, 4, 5, 3
+    x = g.standard_normal((n, m)); wg = g.standard_normal((m, e))
+    w1 = np.repeat(g.standard_normal((1, m, h)), e, axis=0); w2 = np.repeat(g.standard_normal((1, h, m)), e, axis=0)
+    out = O.layer_fwd(x, wg, None, w1, None, w2, e, n, O.ACT_GELU_TANH, O.GATE_EXPERT_CHOICE, 0, np.float64)
+    hh = x @ wg
+    col = np.exp(hh - hh.max(axis=0)); col /= col.sum(axis=0)
+    np.testing.assert_allclose(out["topk_w"], col, rtol=1e-13)
+    dense = dense_ffn_by_loops(x, w1[0], None, w2[0], O.ACT_GELU_TANH)
+    np.testing.assert_allclose(out["y"], col.sum(axis=1, keepdims=True) * dense, rtol=1e-12, atol=1e-14)
+
+
+def test_expert_choice_backward_is_the_token_choice_jacobian_on_the_transposed_problem():
+    """Softmax(KeepTopK(.)) along the tokens of H^T: the logit gradient must equal what the token-choice gate
+    gives when experts and tokens swap roles."""
+    g = rng(520)
+    n, m, e, k = 15, 5, 4, 6
+    x = g.standard_normal((n, m)); wg = g.standard_normal((m, e)); bg = g.standard_normal(e)
+    r = O.route_expert_choice(x, wg, bg, k, np.float64)
+    dtw = g.standard_normal((n, e))
+    dl, dwg, dbg, dx = O.gate_bwd(x, wg, r["logits"], r["topk_idx"], r["pos"], dtw, O.GATE_EXPERT_CHOICE, True)
+    kept = O.keep_top_k(r["logits"].T, k)                                  # [E,k]: the "choices" of each expert
+    dt = np.stack([dtw[kept[i], i] for i in range(e)])                     # upstream gradient in that layout
+    dl_t, _, _, _ = O.gate_bwd(np.zeros((e, 1)), np.zeros((1, n)), r["logits"].T, kept, np.zeros((e, k), np.int32), dt,
+                               O.GATE_SOFTMAX_TOPK, False)
+    np.testing.assert_allclose(dl, dl_t.T, rtol=1e-13, atol=1e-16)
+    np.testing.assert_allclose(dwg, x.T @ dl, rtol=1e-13)
+    np.testing.assert_allclose(dbg, dl.sum(axis=0), rtol=1e-13, atol=1e-16)
+    np.testing.assert_allclose(dx, dl @ wg.T, rtol=1e-13)
+    assert np.abs(dl.sum(axis=0)).max() < 1e-14                            # a softmax Jacobian annihilates constants
