@@ -46,7 +46,9 @@ typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
 typedef enum { MOE_ACT_RELU = 0, MOE_ACT_GELU_TANH = 1, MOE_ACT_SWIGLU = 2, MOE_ACT_GELU_ERF = 3 } moe_act_t;
 
 /* Gate-weight functions of Sec. 2.1 (values of moe_config_t.renormalize). */
-typedef enum { MOE_GATE_SOFTMAX_ALL = 0, MOE_GATE_SOFTMAX_TOPK = 1, MOE_GATE_SIGMOID = 2 } moe_gate_t;
+typedef enum {
+  MOE_GATE_SOFTMAX_ALL = 0, MOE_GATE_SOFTMAX_TOPK = 1, MOE_GATE_SIGMOID = 2, MOE_GATE_EXPERT_CHOICE = 3
+} moe_gate_t;
 
 typedef struct moe_config {
   int32_t n_tokens;         /* N = B*L */
@@ -60,7 +62,12 @@ typedef struct moe_config {
   int32_t renormalize;      /* gate weights, moe_gate_t.  The k experts are always those of the k largest logits.
                                1: G = Softmax(KeepTopK(H, k)) as printed in Sec. 2.1;
                                0: softmax over all E, selected probabilities used as they are;
-                               2: the sigmoid gate of Sec. 2.1 (BASE, StableMoE): weight sigma(H_i) */
+                               2: the sigmoid gate of Sec. 2.1 (BASE, StableMoE): weight sigma(H_i);
+                               3: expert choice (Sec. 2.1), G = Softmax(KeepTopK(H^T, k)): every expert keeps the
+                                  `capacity` tokens with its largest logits (ties: earlier token) and weighs them
+                                  by the softmax over those logits.  A token has one slot per expert, so top_k
+                                  must equal n_experts (hence E <= 8), slot j is expert j, and capacity > 0 is the
+                                  number of tokens per expert.  See moe_route. */
   int32_t add_residual;     /* 1: y = x + MoE(x) (and dx += dy) */
   int32_t accumulate_wgrad; /* 0: expert weight gradients are overwritten; 1: added to */
 } moe_config_t;
@@ -83,6 +90,9 @@ moe_status_t moe_workspace_bytes(const moe_config_t* cfg, size_t* workspace_byte
  *                 tokens in order inside a rank, while the expert has fewer than T rows; else -1
  *   count[e] = rows kept by expert e, offsets = exclusive prefix sum of count (offsets[E] = A)
  *   row_of[t,j] = offsets[e] + pos[t,j] or -1;  src_of_row[row] = t*k + j  (entries >= A: -1)
+ * renormalize=3 (expert choice), k = E: topk_idx[t,j] = j; pos[t,j] = rank of token t among the tokens expert j
+ *   kept, in token order, or -1; topk_w = probs = softmax over the kept logits of the expert's column, 0 elsewhere;
+ *   count[e] = min(capacity, N) for every expert; row_of, offsets, src_of_row as above.
  * in : x [N,M] dtype, w_gate [M,E] dtype, b_gate [E] fp32 or NULL
  * out: logits [N,E] f32, probs [N,E] f32, topk_idx [N,k] i32, topk_w [N,k] f32, pos [N,k] i32,
  *      row_of [N,k] i32, count [E] i32, offsets [E+1] i32, src_of_row [N*k] i32

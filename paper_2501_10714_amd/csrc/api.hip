@@ -36,9 +36,13 @@ moe_status_t check_cfg(const moe_config_t* c) {
   REQUIRE(c->top_k <= c->n_experts, MOE_ERR_INVALID_ARG, "top_k=%d exceeds n_experts=%d", c->top_k, c->n_experts);
   REQUIRE(c->dtype == MOE_F32 || c->dtype == MOE_BF16, MOE_ERR_INVALID_ARG, "unknown dtype %d", c->dtype);
   REQUIRE(c->act >= MOE_ACT_RELU && c->act <= MOE_ACT_GELU_ERF, MOE_ERR_INVALID_ARG, "unknown activation %d", c->act);
-  REQUIRE(c->renormalize >= MOE_GATE_SOFTMAX_ALL && c->renormalize <= MOE_GATE_SIGMOID, MOE_ERR_INVALID_ARG,
+  REQUIRE(c->renormalize >= MOE_GATE_SOFTMAX_ALL && c->renormalize <= MOE_GATE_EXPERT_CHOICE, MOE_ERR_INVALID_ARG,
           "unknown gate-weight function %d", c->renormalize);
   REQUIRE(c->top_k <= 8, MOE_ERR_UNSUPPORTED, "top_k=%d: at most 8 is supported", c->top_k);
+  if (c->renormalize == MOE_GATE_EXPERT_CHOICE)
+    REQUIRE(c->top_k == c->n_experts && c->capacity > 0, MOE_ERR_INVALID_ARG,
+            "expert choice: top_k=%d must equal n_experts=%d (one slot per expert) and capacity=%d must be positive",
+            c->top_k, c->n_experts, c->capacity);
   REQUIRE(c->n_experts <= 256, MOE_ERR_UNSUPPORTED, "n_experts=%d: at most 256 is supported", c->n_experts);
   const int vec = c->dtype == MOE_BF16 ? 8 : 4;
   REQUIRE(c->d_model % vec == 0 && c->d_hidden % vec == 0, MOE_ERR_UNSUPPORTED,
@@ -172,6 +176,7 @@ moe_status_t moe_route_noisy(const moe_config_t* cfg, const void* x, const void*
   NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(w_noise); NOT_NULL(noise); NOT_NULL(logits); NOT_NULL(noise_logits);
   NOT_NULL(probs); NOT_NULL(topk_idx); NOT_NULL(topk_w); NOT_NULL(pos); NOT_NULL(row_of); NOT_NULL(count);
   NOT_NULL(offsets); NOT_NULL(src_of_row);
+  REQUIRE(cfg->renormalize != MOE_GATE_EXPERT_CHOICE, MOE_ERR_UNSUPPORTED, "moe_route_noisy: not with expert choice");
   CHECK_WS(cfg, workspace, workspace_bytes_);
   return launch_route_noisy(*cfg, x, w_gate, b_gate, w_noise, noise, logits, noise_logits, probs, topk_idx, topk_w, pos,
                             row_of, count, offsets, src_of_row, workspace, as_stream(stream));
@@ -185,6 +190,7 @@ moe_status_t moe_route_noisy_bwd(const moe_config_t* cfg, const void* x, const v
   CHECK_CFG(cfg);
   NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(w_noise); NOT_NULL(noise); NOT_NULL(noise_logits); NOT_NULL(probs);
   NOT_NULL(topk_idx); NOT_NULL(pos); NOT_NULL(dtopk_w); NOT_NULL(dw_gate); NOT_NULL(dw_noise); NOT_NULL(dx);
+  REQUIRE(cfg->renormalize != MOE_GATE_EXPERT_CHOICE, MOE_ERR_UNSUPPORTED, "moe_route_noisy_bwd: not with expert choice");
   CHECK_WS(cfg, workspace, workspace_bytes_);
   return launch_route_noisy_bwd(*cfg, x, w_gate, w_noise, noise, noise_logits, probs, topk_idx, pos, dtopk_w, dw_gate,
                                 db_gate, dw_noise, dx, workspace, as_stream(stream));
@@ -194,6 +200,7 @@ static moe_status_t check_xmoe(const char* fn, const moe_config_t* cfg, int32_t 
                                size_t workspace_bytes_) {
   REQUIRE(d_proj >= 4 && d_proj <= 256 && d_proj % 4 == 0, MOE_ERR_UNSUPPORTED,
           "%s: d_proj=%d must be a multiple of 4 in 4..256", fn, d_proj);
+  REQUIRE(cfg->renormalize != MOE_GATE_EXPERT_CHOICE, MOE_ERR_UNSUPPORTED, "%s: not with expert choice", fn);
   REQUIRE(workspace != nullptr, MOE_ERR_INVALID_ARG, "%s: argument 'workspace' is NULL", fn);
   const size_t need = route_xmoe_workspace_bytes(*cfg, d_proj);
   REQUIRE(workspace_bytes_ >= need, MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes, need %zu", fn, workspace_bytes_, need);

@@ -813,6 +813,169 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
   return MOE_OK;
 }
 
+// ----------------------------------------------------------------------------- expert choice (Sec. 2.1)
+// G(I) = Softmax(KeepTopK((I.W_g)^T, k)): every expert keeps the k tokens with its largest logits and weighs
+// them by the softmax over those logits.  One block per expert walks its column of the logits: a radix select
+// (four rounds of 8 bits on an order-preserving integer key) finds the k-th largest value, two prefix counts in
+// token order then give every kept token its row (tokens above the threshold, and the earliest of those equal to
+// it), and the softmax needs one sum.  Nothing depends on the order in which threads run.
+constexpr int kEcThreads = 1024;
+
+// larger float <=> larger key; -0 and +0 get the same key
+__device__ __forceinline__ uint32_t ec_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// number of threads before this one (in thread order) whose flag is set, and the block's count; every thread calls it
+__device__ __forceinline__ int ec_block_rank(bool flag, int* wave_tot, int& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const unsigned long long b = __ballot(flag);
+  __syncthreads();  // the previous use of wave_tot is over
+  if (lane == 0) wave_tot[wave] = __popcll(b);
+  __syncthreads();
+  int before = 0, tot = 0;
+  for (int w = 0; w < kEcThreads / 64; ++w) {
+    const int c = wave_tot[w];
+    before += w < wave ? c : 0;
+    tot += c;
+  }
+  total = tot;
+  return before + __popcll(b & ((1ull << lane) - 1ull));
+}
+
+// sum over the block, lanes then waves in order (the same on every run); every thread calls it and gets the sum
+__device__ __forceinline__ float ec_block_sum(float v, float* wave_sum) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float s = 0.0f;
+  for (int w = 0; w < kEcThreads / 64; ++w) s += wave_sum[w];
+  return s;
+}
+
+__global__ __launch_bounds__(kEcThreads) void ec_select_kernel(const float* __restrict__ logits, float* __restrict__ probs,
+                                                               int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                               int32_t* __restrict__ pos, int32_t* __restrict__ row_of,
+                                                               int32_t* __restrict__ count, int32_t* __restrict__ offsets,
+                                                               int32_t* __restrict__ src_of_row, int n_tokens,
+                                                               int n_experts, int k_tokens) {
+  __shared__ int hist[256];
+  __shared__ int s_bucket, s_need;
+  __shared__ int wave_tot[kEcThreads / 64];
+  __shared__ float wave_sum[kEcThreads / 64];
+  __shared__ float wave_max[kEcThreads / 64];
+  const int e = blockIdx.x, tid = threadIdx.x;
+  const int k = min(k_tokens, n_tokens);
+
+  // the k-th largest key of the column, and how many of the keys equal to it are kept
+  uint32_t prefix = 0u, mask = 0u;
+  int need = k;
+  float mx = -INFINITY;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int t = tid; t < n_tokens; t += kEcThreads) {
+      const float l = logits[(size_t)t * n_experts + e];
+      mx = fmaxf(mx, l);
+      const uint32_t key = ec_key(l);
+      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {  // from the top bucket down to the one that holds the need-th largest
+      int acc = 0, b = 255;
+      while (b > 0 && acc + hist[b] < need) { acc += hist[b]; --b; }
+      s_bucket = b;
+      s_need = need - acc;
+    }
+    __syncthreads();
+    prefix |= (uint32_t)s_bucket << shift;
+    mask |= 0xFFu << shift;
+    need = s_need;
+    __syncthreads();  // hist, s_bucket, s_need are rewritten in the next round
+  }
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  if ((tid & 63) == 0) wave_max[tid >> 6] = mx;
+  __syncthreads();
+  for (int w = 0; w < kEcThreads / 64; ++w) mx = fmaxf(mx, wave_max[w]);
+
+  // rows in token order, and the sum of the softmax
+  float part = 0.0f;
+  int run_eq = 0, run_sel = 0;
+  for (int base = 0; base < n_tokens; base += kEcThreads) {
+    const int t = base + tid;
+    const bool live = t < n_tokens;
+    const float l = live ? logits[(size_t)t * n_experts + e] : 0.0f;
+    const uint32_t key = ec_key(l);
+    const bool eq = live && key == prefix;
+    int tot_eq, tot_sel;
+    const int eq_rank = run_eq + ec_block_rank(eq, wave_tot, tot_eq);
+    const bool sel = live && (key > prefix || (eq && eq_rank < need));
+    const int p = run_sel + ec_block_rank(sel, wave_tot, tot_sel);
+    run_eq += tot_eq;
+    run_sel += tot_sel;
+    if (live) {
+      const size_t i = (size_t)t * n_experts + e;
+      topk_idx[i] = e;
+      pos[i] = sel ? p : -1;
+      row_of[i] = sel ? e * k + p : -1;
+      if (sel) {
+        src_of_row[e * k + p] = t * n_experts + e;
+        part += expf(l - mx);
+      }
+    }
+  }
+  const float sum = ec_block_sum(part, wave_sum);
+  for (int t = tid; t < n_tokens; t += kEcThreads) {  // each thread meets the tokens it handled above
+    const size_t i = (size_t)t * n_experts + e;
+    const float w = pos[i] >= 0 ? expf(logits[i] - mx) / sum : 0.0f;
+    topk_w[i] = w;
+    probs[i] = w;
+  }
+  if (tid == 0) {
+    count[e] = k;
+    offsets[e] = e * k;
+    if (e == n_experts - 1) offsets[n_experts] = n_experts * k;
+  }
+  // rows past the last expert's have no source
+  for (int r = n_experts * k + e * kEcThreads + tid; r < n_tokens * n_experts; r += n_experts * kEcThreads) src_of_row[r] = -1;
+}
+
+// dl[t,e] = p[t,e] (g[t,e] - c_e) on the kept tokens of expert e, 0 elsewhere; c_e = sum over them of p g
+// (the softmax runs down the column).  One block per expert.
+__global__ __launch_bounds__(kEcThreads) void ec_dlogits_kernel(const float* __restrict__ probs,
+                                                                const int32_t* __restrict__ pos,
+                                                                const float* __restrict__ dtopk_w, float* __restrict__ dl,
+                                                                int n_tokens, int n_experts) {
+  __shared__ float wave_sum[kEcThreads / 64];
+  const int e = blockIdx.x;
+  float part = 0.0f;
+  for (int t = threadIdx.x; t < n_tokens; t += kEcThreads) {
+    const size_t i = (size_t)t * n_experts + e;
+    if (pos[i] >= 0) part = fmaf(probs[i], dtopk_w[i], part);
+  }
+  const float c = ec_block_sum(part, wave_sum);
+  for (int t = threadIdx.x; t < n_tokens; t += kEcThreads) {
+    const size_t i = (size_t)t * n_experts + e;
+    dl[i] = pos[i] >= 0 ? probs[i] * (dtopk_w[i] - c) : 0.0f;
+  }
+}
+
+template <typename T>
+moe_status_t route_ec_t(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
+                        float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
+                        int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
+  moe_status_t st = route_t<T>(c, x, w_gate, b_gate, logits, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                               nullptr, ws, nullptr, nullptr, kGateLogitsOnly, s);
+  if (st != MOE_OK) return st;
+  hipLaunchKernelGGL(ec_select_kernel, dim3(c.n_experts), dim3(kEcThreads), 0, s, (const float*)logits, probs, topk_idx,
+                     topk_w, pos, row_of, count, offsets, src_of_row, c.n_tokens, c.n_experts, c.capacity);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
+}
+
 // ----------------------------------------------------------------------------- X-MoE gate (Sec. 2.1)
 // s_i = cos(W_proj I, W_g[:, i]): the token is projected to D dimensions (the gate kernel with W_proj in the
 // place of W_g, logits only), projection and expert embeddings are scaled to unit length, and the scores
@@ -1008,6 +1171,11 @@ size_t route_bwd_workspace_bytes(const moe_config_t& c) { return route_bwd_plan(
 moe_status_t launch_route(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
                           float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
                           int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s) {
+  if (c.renormalize == MOE_GATE_EXPERT_CHOICE)
+    return c.dtype == MOE_BF16 ? route_ec_t<bf16_t>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
+                                                    offsets, src_of_row, ws, s)
+                               : route_ec_t<float>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
+                                                   offsets, src_of_row, ws, s);
   return c.dtype == MOE_BF16 ? route_t<bf16_t>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
                                                offsets, src_of_row, ws, nullptr, nullptr, kGateFull, s)
                              : route_t<float>(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count,
@@ -1035,9 +1203,17 @@ moe_status_t launch_route_noisy(const moe_config_t& c, const void* x, const void
 moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                               const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                               float* db_gate, void* dx, void* ws, hipStream_t s) {
+  const float* dl_ext = nullptr;
+  if (c.renormalize == MOE_GATE_EXPERT_CHOICE) {  // its own Jacobian (down the columns), then the gate's products
+    float* dl = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + route_bwd_plan(c).off_dl);
+    hipLaunchKernelGGL(ec_dlogits_kernel, dim3(c.n_experts), dim3(kEcThreads), 0, s, probs, pos, dtopk_w, dl, c.n_tokens,
+                       c.n_experts);
+    MOE_CHECK_LAUNCH();
+    dl_ext = dl;
+  }
   return c.dtype == MOE_BF16
-             ? route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, nullptr, s)
-             : route_bwd_f32(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, nullptr, s);
+             ? route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, dl_ext, s)
+             : route_bwd_f32(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, dl_ext, s);
 }
 
 // Backward of the noisy gate: the ordinary gate backward for W_g (dH = dlogits), then the same products for

@@ -12,7 +12,7 @@ from test_gpu_parity import CASES
 pytestmark = pytest.mark.gpu
 
 NAMES = ["tiny_full", "f32_ragged", "gpt2_small", "mixtral_small", "fine_small", "switch_small", "erf_odd",
-         "k32_pipeline", "sigmoid_glu"]
+         "k32_pipeline", "sigmoid_glu", "expert_choice_glu"]
 
 
 def same_bits(a, b):

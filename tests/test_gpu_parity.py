@@ -42,6 +42,10 @@ CASES = {
     # the largest expert count and top-k the library takes: the gate kernel then holds fewer experts per pass
     "experts_256_bf16": S.scaled(W["finegrained"], N=300, M=64, H=64, E=256, k=8, seed=33),
     "experts_130_f32": S.scaled(W["tiny"], N=200, M=40, H=64, E=130, k=8, f=1.5, seed=34),
+    # expert choice (Sec. 2.1): every expert keeps ceil(f N) tokens; one slot per expert, so k = E
+    "expert_choice_glu": S.scaled(W["mixtral"], N=2500, M=128, H=192, E=8, k=8, f=0.25, renormalize=3, seed=35),
+    "expert_choice_f32": S.scaled(W["tiny"], N=333, M=64, H=96, E=5, k=5, f=0.3, renormalize=3, seed=36),
+    "expert_choice_all_tokens": S.scaled(W["tiny"], N=70, M=32, H=64, E=3, k=3, f=2.0, renormalize=3, seed=37),
 }
 
 
@@ -174,7 +178,12 @@ def test_route_bwd(name, solved):
             if fwd["pos"][t, j] >= 0:
                 g[t, fwd["topk_idx"][t, j]] = dtw32[t, j]
     p = probs32.astype(np.float64)
-    dl = g * p * (1.0 - p) if w.renormalize == 2 else p * (g - (g * p).sum(1, keepdims=True))
+    if w.renormalize == 2:
+        dl = g * p * (1.0 - p)
+    elif w.renormalize == 3:                                     # expert choice: the softmax runs down the columns
+        dl = p * (g - (g * p).sum(0, keepdims=True))
+    else:
+        dl = p * (g - (g * p).sum(1, keepdims=True))
     tol = TOL[w.dtype]
     assert rel_err(to_np(b.dw_gate), f["x"].T @ dl) <= tol
     assert rel_err(to_np(b.dx), S.to_f64(base) + dl @ f["w_gate"].T) <= tol
@@ -274,3 +283,31 @@ def test_exact_ties_go_to_the_lower_expert():
     assert_routing_equal(got, fwd)
     idx = fwd["topk_idx"]
     assert not np.any((idx[:, 0] == 3) | (idx[:, 0] == 5))
+
+
+def test_expert_choice_argument_checks():
+    """One slot per expert: top_k must equal n_experts, and the capacity is the number of tokens per expert."""
+    w = CASES["expert_choice_f32"]
+    with pytest.raises(moe.MoeError, match="expert choice"):
+        moe.moe_workspace_bytes(make_cfg(S.scaled(w, k=2)))
+    with pytest.raises(moe.MoeError, match="expert choice"):
+        moe.moe_workspace_bytes(make_cfg(w, capacity=0))
+
+
+def test_expert_choice_ties_and_signed_zeros():
+    """Equal logits go to the earlier token, and -0 ties with +0: x = 0 rows give logits of exactly 0 (of either sign
+    through the bias), identical rows give identical logits."""
+    w = S.scaled(CASES["expert_choice_f32"], N=40, M=8, E=2, k=2, f=0.25, seed=38)
+    x = S.to_f64(S.draw_x(w)).astype(np.float32)
+    x[5] = x[3]; x[9] = x[3]; x[20] = x[3]                    # four equal rows
+    x[30:] = 0.0                                              # ten zero rows: logit = b_gate exactly
+    wg = S.to_f64(S.draw_w_gate(w)).astype(np.float32)
+    for bg in (np.array([0.0, -0.0], np.float32), np.array([10.0, -10.0], np.float32), np.array([-0.0, 5.0], np.float32)):
+        ref = O.route(x.astype(np.float64), wg.astype(np.float64), bg.astype(np.float64), w.k, 10, 3)
+        cfg = make_cfg(w, capacity=10)
+        b = Buffers(w, cfg)
+        moe.moe_route(cfg, to_dev(x), to_dev(wg), to_dev(bg), b.logits, b.probs, b.topk_idx, b.topk_w, b.pos, b.row_of,
+                      b.count, b.offsets, b.src_of_row, b.ws)
+        torch.cuda.synchronize()
+        assert_routing_equal(routing_dict(b), ref)
+        assert rel_err(to_np(b.topk_w), ref["topk_w"]) <= 1e-5
