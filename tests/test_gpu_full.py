@@ -93,3 +93,86 @@ def test_large_shapes_sampled(name):
         assert rel_err(to_np(b.db_gate), dl.sum(0)) <= tol
     others = np.setdiff1d(np.arange(w.N), toks)[:4096]
     assert torch.count_nonzero(b.dx[torch.from_numpy(others).cuda()]).item() == 0   # no gradient without dy
+
+
+def _timed(fn, reps=5):
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def test_xmoe_gate_at_the_mixtral_token_shape():
+    """X-MoE gate (Sec. 2.1) at N, M, E, k of the Mixtral shape with a 256-wide projection: projection, scores and
+    routing bit exact in full, gradients in full within the bf16 tolerance."""
+    w = S.scaled(S.WORKLOADS["mixtral"], H=64, seed=61)
+    d_proj = 256
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    x, wp, wg, dtw = S.draw_x(w), S.draw_w_proj(w, d_proj), S.draw_w_embed(w, d_proj), S.draw_dtopk_w(w)
+    ref = O.route_xmoe(S.to_f64(x), S.to_f64(wp), S.to_f64(wg), w.k, cap_of(w), w.renormalize)
+    ws = torch.empty(moe.moe_route_xmoe_workspace_bytes(cfg, d_proj), dtype=torch.uint8, device="cuda")
+    proj = torch.empty(w.N, d_proj, dtype=torch.float32, device="cuda")
+    xd, wpd, wgd = to_dev(x), to_dev(wp), to_dev(wg)
+    fwd = lambda: moe.moe_route_xmoe(cfg, xd, wpd, wgd, d_proj, proj, b.logits, b.probs, b.topk_idx, b.topk_w, b.pos,
+                                     b.row_of, b.count, b.offsets, b.src_of_row, ws)
+    t_fwd = _timed(fwd)
+    assert np.array_equal(proj.cpu().numpy(), ref["proj"])
+    assert np.array_equal(b.logits.cpu().numpy(), ref["logits"])
+    assert_routing_equal({n: to_np(getattr(b, n)) for n in ROUTING}, ref)
+    assert rel_err(to_np(b.topk_w), ref["topk_w"]) <= 1e-5
+
+    ds, dwp, dwg, dx = O.gate_bwd_xmoe(S.to_f64(x), S.to_f64(wp), S.to_f64(wg), ref["proj"], ref["logits"], ref["topk_idx"],
+                                       ref["pos"], dtw.astype(np.float64), w.renormalize)
+    dw_proj = torch.empty(w.M, d_proj, dtype=b.dw_gate.dtype, device="cuda")
+    dw_gate = torch.empty(d_proj, w.E, dtype=b.dw_gate.dtype, device="cuda")
+    args = (to_dev(ref["proj"]), to_dev(ref["probs"].astype(np.float32)), to_dev(ref["topk_idx"]), to_dev(ref["pos"]), to_dev(dtw))
+
+    def bwd():
+        b.dx.zero_()
+        moe.moe_route_xmoe_bwd(cfg, xd, wpd, wgd, d_proj, *args, dw_proj, dw_gate, b.dx, ws)
+    t_bwd = _timed(bwd)
+    tol = TOL[w.dtype]
+    assert rel_err(to_np(dw_proj), dwp) <= tol
+    assert rel_err(to_np(dw_gate), dwg) <= tol
+    assert rel_err(to_np(b.dx), dx) <= tol
+    print(f"\nX-MoE gate, N={w.N} M={w.M} D={d_proj} E={w.E}: forward {t_fwd:.3f} ms, backward (with dx clear) {t_bwd:.3f} ms")
+
+
+def test_expert_choice_gate_at_the_mixtral_token_shape():
+    """Expert choice (Sec. 2.1) at N, M, E of the Mixtral shape, every expert keeping N/4 tokens: routing bit exact
+    in full, weights and gate gradients in full."""
+    w = S.scaled(S.WORKLOADS["mixtral"], H=64, k=8, f=0.25, renormalize=3, seed=62)
+    cfg = make_cfg(w)
+    assert cfg.capacity == w.N // 4
+    b = Buffers(w, cfg)
+    x, wg = S.draw_x(w), S.draw_w_gate(w)
+    dtw = S.draw_dtopk_w(w)
+    ref = O.route(S.to_f64(x), S.to_f64(wg), None, w.k, cap_of(w), w.renormalize)
+    xd, wgd = to_dev(x), to_dev(wg)
+    fwd = lambda: moe.moe_route(cfg, xd, wgd, None, b.logits, b.probs, b.topk_idx, b.topk_w, b.pos, b.row_of, b.count,
+                                b.offsets, b.src_of_row, b.ws)
+    t_fwd = _timed(fwd)
+    assert np.array_equal(b.logits.cpu().numpy(), ref["logits"])
+    assert_routing_equal({n: to_np(getattr(b, n)) for n in ROUTING}, ref)
+    assert rel_err(to_np(b.topk_w), ref["topk_w"]) <= 1e-5
+    assert rel_err(to_np(b.probs), ref["probs"]) <= 1e-5
+
+    dl, dwg, _, dx = O.gate_bwd(S.to_f64(x), S.to_f64(wg), ref["logits"], ref["topk_idx"], ref["pos"], dtw.astype(np.float64),
+                                w.renormalize, False)
+    args = (to_dev(ref["probs"].astype(np.float32)), to_dev(ref["topk_idx"]), to_dev(ref["pos"]), to_dev(dtw))
+
+    def bwd():
+        b.dx.zero_()
+        moe.moe_route_bwd(cfg, xd, wgd, *args, b.dw_gate, None, b.dx, b.ws)
+    t_bwd = _timed(bwd)
+    tol = TOL[w.dtype]
+    assert rel_err(to_np(b.dw_gate), dwg) <= tol
+    assert rel_err(to_np(b.dx), dx) <= tol
+    print(f"\nexpert-choice gate, N={w.N} M={w.M} E={w.E}, {cfg.capacity} tokens per expert: forward {t_fwd:.3f} ms, "
+          f"backward (with dx clear) {t_bwd:.3f} ms")
