@@ -31,19 +31,31 @@ template <> struct Elem<bf16_t> {
 };
 
 // 16-byte vector of elements, widened to fp32 lanes
+// 16-byte accesses marked non-temporal: for data that is read or written once per kernel and not needed in
+// the caches afterwards (the rows the ordering kernels stream through)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load16_nt(const void* p) {
+  const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(r[0], r[1], r[2], r[3]);
+}
+__device__ __forceinline__ void store16_nt(void* p, const uint4& v) {
+  const u32x4_t r = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(r, reinterpret_cast<u32x4_t*>(p));
+}
+
 template <typename T> struct Vec16;
 template <> struct Vec16<float> {
   float v[4];
-  __device__ __forceinline__ void load(const float* p) {
-    float4 r = *reinterpret_cast<const float4*>(p);
-    v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+  __device__ __forceinline__ void set(const uint4& r) {
+    v[0] = __uint_as_float(r.x); v[1] = __uint_as_float(r.y); v[2] = __uint_as_float(r.z); v[3] = __uint_as_float(r.w);
   }
+  __device__ __forceinline__ void load(const float* p) { set(*reinterpret_cast<const uint4*>(p)); }
+  __device__ __forceinline__ void load_nt(const float* p) { set(load16_nt(p)); }
   __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
 };
 template <> struct Vec16<bf16_t> {
   float v[8];
-  __device__ __forceinline__ void load(const bf16_t* p) {
-    uint4 r = *reinterpret_cast<const uint4*>(p);
+  __device__ __forceinline__ void set(const uint4& r) {
     uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -51,6 +63,8 @@ template <> struct Vec16<bf16_t> {
       v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
     }
   }
+  __device__ __forceinline__ void load(const bf16_t* p) { set(*reinterpret_cast<const uint4*>(p)); }
+  __device__ __forceinline__ void load_nt(const bf16_t* p) { set(load16_nt(p)); }
   __device__ __forceinline__ void store(bf16_t* p) const {
     uint32_t w[4];
 #pragma unroll

@@ -4,6 +4,8 @@
 // read once and fanned out to (or gathered from) its k expert rows, so the traffic is the
 // algorithmic minimum  N*M*b + A*M*b.  Rows move as 16-byte vectors; a row is covered by a group
 // of `tpr` consecutive lanes (a power of two), so one wave touches whole contiguous rows.
+// Which accesses are marked non-temporal was chosen by timing each kernel inside the layer (the cache state
+// its neighbours leave matters): the stores of the ordering function, the loads of the three gathers.
 #include "common.h"
 
 namespace moe {
@@ -42,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void dispatch_kernel(const T* __restrict__ 
     uint4 v = src[c];
 #pragma unroll
     for (int j = 0; j < kMaxK; ++j)
-      if (rows[j] >= 0) reinterpret_cast<uint4*>(xe + (size_t)rows[j] * d_model)[c] = v;
+      if (rows[j] >= 0) store16_nt(reinterpret_cast<uint4*>(xe + (size_t)rows[j] * d_model) + c, v);
   }
 }
 
@@ -104,14 +106,14 @@ __global__ __launch_bounds__(kBlock) void gather_sum_kernel(const T* __restrict_
     for (int j = 0; j < kMaxK; ++j) {
       if (rows[j] >= 0) {
         Vec16<T> v;
-        v.load(src + (size_t)rows[j] * d_model + c * V);
+        v.load_nt(src + (size_t)rows[j] * d_model + c * V);
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[i] = kWeighted ? fmaf(sc[j], v.v[i], acc[i]) : acc[i] + v.v[i];
       }
     }
     if (res != nullptr) {
       Vec16<T> r;
-      r.load(res + (size_t)t * d_model + c * V);
+      r.load_nt(res + (size_t)t * d_model + c * V);
 #pragma unroll
       for (int i = 0; i < V; ++i) acc[i] += r.v[i];
     }
@@ -147,12 +149,12 @@ __global__ __launch_bounds__(kBlock) void combine_bwd_kernel(const T* __restrict
   if (live) {
     for (int c = lane; c < chunks; c += tpr) {
       Vec16<T> g;
-      g.load(dy + (size_t)t * d_model + c * V);
+      g.load_nt(dy + (size_t)t * d_model + c * V);
 #pragma unroll
       for (int j = 0; j < kMaxK; ++j) {
         if (rows[j] >= 0) {
           Vec16<T> qv, o;
-          qv.load(q + (size_t)rows[j] * d_model + c * V);
+          qv.load_nt(q + (size_t)rows[j] * d_model + c * V);
 #pragma unroll
           for (int i = 0; i < V; ++i) {
             dot[j] = fmaf(g.v[i], qv.v[i], dot[j]);
