@@ -90,3 +90,53 @@ def test_xmoe_argument_checks():
     with pytest.raises(moe.MoeError, match="workspace"):
         moe.moe_route_xmoe(cfg, x, wp, wg, d, proj, b.logits, b.probs, b.topk_idx, b.topk_w, b.pos, b.row_of, b.count,
                            b.offsets, b.src_of_row, small)
+
+
+@pytest.mark.parametrize("name", ["xmoe_bf16_topk", "xmoe_f32_sigmoid"])
+def test_xmoe_layer_through_the_stage_calls(name):
+    """A whole MoE layer with the X-MoE gate, forward and backward, chained from the per-stage entry points
+    (route -> ordering -> experts -> I-ordering and back), against the same chain of oracle functions."""
+    w, d = CASES[name]
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    f = lambda a: None if a is None else S.to_f64(a)
+    x, wp, wg = S.draw_x(w), S.draw_w_proj(w, d), S.draw_w_embed(w, d)
+    dw = S.draw_all(w)
+    w1, w3, w2, dy = dw["w1"], dw["w3"], dw["w2"], dw["dy"]
+    # ---- oracle
+    r = O.route_xmoe(f(x), f(wp), f(wg), w.k, cap_of(w), w.renormalize)
+    n_rows = int(r["offsets"][-1])
+    xe = O.order(f(x), r["row_of"], n_rows)
+    q, saved = O.expert_ffn(xe, r["offsets"], f(w1), f(w3), f(w2), w.act)
+    y = O.inverse_order(q, r["topk_w"], r["row_of"], f(x) if w.add_residual else None)
+    dq, dtw = O.inverse_order_bwd(f(dy), q, r["topk_w"], r["row_of"])
+    dxe, dw1, dw3, dw2 = O.expert_ffn_bwd(dq, xe, r["offsets"], f(w1), f(w3), f(w2), saved, w.act)
+    dx = O.order_bwd(dxe, r["row_of"], f(dy) if w.add_residual else None)
+    _, dwp, dwg, dx_gate = O.gate_bwd_xmoe(f(x), f(wp), f(wg), r["proj"], r["logits"], r["topk_idx"], r["pos"], dtw,
+                                           w.renormalize)
+    # ---- the library, stage by stage
+    ws_x = torch.empty(moe.moe_route_xmoe_workspace_bytes(cfg, d), dtype=torch.uint8, device="cuda")
+    proj = torch.empty(w.N, d, dtype=torch.float32, device="cuda")
+    xd, wpd, wgd, w1d, w3d, w2d, dyd = (None if a is None else to_dev(a) for a in (x, wp, wg, w1, w3, w2, dy))
+    moe.moe_route_xmoe(cfg, xd, wpd, wgd, d, proj, b.logits, b.probs, b.topk_idx, b.topk_w, b.pos, b.row_of, b.count,
+                       b.offsets, b.src_of_row, ws_x)
+    moe.moe_dispatch(cfg, xd, b.row_of, b.xe)
+    moe.moe_expert_ffn_fwd(cfg, b.xe, b.offsets, w1d, w3d, w2d, b.q, b.a1, b.a3, b.hh, b.ws)
+    moe.moe_combine(cfg, b.q, b.topk_w, b.row_of, xd if w.add_residual else None, b.y)
+    moe.moe_combine_bwd(cfg, dyd, b.q, b.topk_w, b.row_of, b.dq, b.dtopk_w)
+    moe.moe_expert_ffn_bwd(cfg, b.dq, b.xe, b.offsets, w1d, w3d, w2d, b.a1, b.a3, b.hh, b.dxe, b.dw1, b.dw3, b.dw2, b.ws)
+    moe.moe_dispatch_bwd(cfg, b.dxe, b.row_of, dyd if w.add_residual else None, b.dx)
+    dw_proj = torch.empty(w.M, d, dtype=b.dw_gate.dtype, device="cuda")
+    dw_gate = torch.empty(d, w.E, dtype=b.dw_gate.dtype, device="cuda")
+    moe.moe_route_xmoe_bwd(cfg, xd, wpd, wgd, d, proj, b.probs, b.topk_idx, b.pos, b.dtopk_w, dw_proj, dw_gate, b.dx, ws_x)
+    torch.cuda.synchronize()
+    assert_routing_equal({n: to_np(getattr(b, n)) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}, r)
+    tol = TOL[w.dtype]
+    assert rel_err(to_np(b.y), y) <= tol
+    assert rel_err(to_np(b.dx), dx + dx_gate) <= tol
+    assert rel_err(to_np(dw_proj), dwp) <= tol
+    assert rel_err(to_np(dw_gate), dwg) <= tol
+    assert rel_err(to_np(b.dw1), dw1) <= tol
+    assert rel_err(to_np(b.dw2), dw2) <= tol
+    if w.gated:
+        assert rel_err(to_np(b.dw3), dw3) <= tol
