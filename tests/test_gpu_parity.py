@@ -311,3 +311,29 @@ def test_expert_choice_ties_and_signed_zeros():
         torch.cuda.synchronize()
         assert_routing_equal(routing_dict(b), ref)
         assert rel_err(to_np(b.topk_w), ref["topk_w"]) <= 1e-5
+
+
+def test_nan_logits_still_give_valid_routing():
+    """Non-finite inputs are outside the contract, but the routing they produce must stay inside the tensors:
+    every token still gets k distinct experts in range, and counts, offsets and the two index maps agree."""
+    w = S.scaled(CASES["f32_ragged"], N=200, E=6, k=3, f=None, seed=39)
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    x = S.to_f64(S.draw_x(w)).astype(np.float32)
+    wg = S.to_f64(S.draw_w_gate(w)).astype(np.float32)
+    x[7, :] = np.nan            # every logit of token 7 is NaN
+    x[50, 3] = np.inf           # inf * weights of both signs: a mix of +inf, -inf (and NaN through the sum)
+    wg[2, 4] = np.nan           # column 4 is NaN for every token
+    moe.moe_route(cfg, to_dev(x), to_dev(wg), None, b.logits, b.probs, b.topk_idx, b.topk_w, b.pos, b.row_of, b.count,
+                  b.offsets, b.src_of_row, b.ws)
+    torch.cuda.synchronize()
+    idx, pos, row_of = to_np(b.topk_idx).astype(int), to_np(b.pos).astype(int), to_np(b.row_of).astype(int)
+    count, offsets, src = to_np(b.count).astype(int), to_np(b.offsets).astype(int), to_np(b.src_of_row).astype(int)
+    assert idx.min() >= 0 and idx.max() < w.E
+    assert all(len(set(row)) == w.k for row in idx.tolist())
+    assert np.array_equal(count, np.bincount(idx.reshape(-1), minlength=w.E))      # nothing dropped (no capacity)
+    assert np.array_equal(offsets, np.concatenate([[0], np.cumsum(count)]))
+    assert sorted(row_of.reshape(-1).tolist()) == list(range(w.N * w.k))
+    for t in range(w.N):
+        for j in range(w.k):
+            assert row_of[t, j] == offsets[idx[t, j]] + pos[t, j] and src[row_of[t, j]] == t * w.k + j
