@@ -194,6 +194,25 @@ moe_status_t moe_layer_bwd_chunked(const moe_config_t* cfg, const void* dy, cons
                                    void* dx, void* dw_gate, float* db_gate, void* dw1, void* dw3, void* dw2,
                                    void* workspace, size_t workspace_bytes, int32_t n_chunks, void* stream);
 
+/* The layer after the gate, for any gate (Sec. 3.1 keeps Gate, Order and Expert as separate sub-modules):
+ * ordering, experts and I-ordering on a routing that is already in `saved`.  The caller first runs one of the
+ * moe_route* calls (or a gate of its own) with the output pointers set to the routing tensors inside `saved`
+ * (moe_saved_offset: LOGITS, PROBS, TOPK_IDX, TOPK_W, POS, ROW_OF, COUNT, OFFSETS, SRC_OF_ROW), on the same
+ * stream.  n_chunks, aux_stream as moe_layer_fwd_chunked (n_chunks = 1: the plain layer).
+ * out: y [N,M]; the activation tensors of `saved`. */
+moe_status_t moe_layer_fwd_routed(const moe_config_t* cfg, const void* x, const void* w1, const void* w3,
+                                  const void* w2, void* y, void* saved, size_t saved_bytes, void* workspace,
+                                  size_t workspace_bytes, int32_t n_chunks, void* stream, void* aux_stream);
+
+/* Backward of the same part, i.e. of everything but the gate.
+ * out: dx [N,M] (OVERWRITTEN: the experts' share, plus dy with add_residual), dw1, dw3, dw2 as moe_layer_bwd,
+ *      dtopk_w [N,k] f32: the gradient of the gate weights (0 for dropped choices).  The gate's own backward
+ *      (moe_route_bwd, moe_route_noisy_bwd, moe_route_xmoe_bwd, ...) takes dtopk_w and adds its share to dx. */
+moe_status_t moe_layer_bwd_routed(const moe_config_t* cfg, const void* dy, const void* w1, const void* w3,
+                                  const void* w2, const void* saved, size_t saved_bytes, void* dx, void* dw1,
+                                  void* dw3, void* dw2, float* dtopk_w, void* workspace, size_t workspace_bytes,
+                                  int32_t n_chunks, void* stream);
+
 /* Where inside `saved` a tensor lives (for inspection and tests).  Host function. */
 typedef enum {
   MOE_SAVED_LOGITS = 0, MOE_SAVED_PROBS, MOE_SAVED_TOPK_IDX, MOE_SAVED_TOPK_W, MOE_SAVED_POS, MOE_SAVED_ROW_OF,

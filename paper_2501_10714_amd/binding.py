@@ -22,7 +22,7 @@ ENTRY_POINTS = ["moe_capacity", "moe_workspace_bytes", "moe_route", "moe_dispatc
                 "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_combine", "moe_combine_bwd", "moe_route_bwd",
                 "moe_layer_fwd", "moe_layer_bwd", "moe_layer_fwd_chunked", "moe_layer_bwd_chunked", "moe_saved_offset",
                 "moe_pipeline_time", "moe_find_pipeline_degree", "moe_route_noisy", "moe_route_noisy_bwd", "moe_route_xmoe_workspace_bytes",
-                "moe_route_xmoe", "moe_route_xmoe_bwd", "moe_last_error"]
+                "moe_route_xmoe", "moe_route_xmoe_bwd", "moe_layer_fwd_routed", "moe_layer_bwd_routed", "moe_last_error"]
 MAX_CHUNKS = 16  # MOE_MAX_CHUNKS
 
 
@@ -225,3 +225,16 @@ def moe_route_xmoe_bwd(cfg, x, w_proj, w_gate, d_proj, proj, probs, topk_idx, po
     _check(load().moe_route_xmoe_bwd(C.byref(cfg), _p(x), _p(w_proj), _p(w_gate), C.c_int32(d_proj), _p(proj), _p(probs),
                                      _p(topk_idx), _p(pos), _p(dtopk_w), _p(dw_proj), _p(dw_gate), _p(dx), _p(ws),
                                      _sz(ws), _stream()))
+
+
+def moe_layer_fwd_routed(cfg, x, w1, w3, w2, y, saved, ws, n_chunks=1, aux_stream=None):
+    """The layer after the gate; the routing tensors of `saved` were filled by a moe_route* call (see saved_view)."""
+    aux = C.c_void_p(None if aux_stream is None else aux_stream.cuda_stream)
+    _check(load().moe_layer_fwd_routed(C.byref(cfg), _p(x), _p(w1), _p(w3), _p(w2), _p(y), _p(saved), _sz(saved), _p(ws),
+                                       _sz(ws), C.c_int32(n_chunks), _stream(), aux))
+
+
+def moe_layer_bwd_routed(cfg, dy, w1, w3, w2, saved, dx, dw1, dw3, dw2, dtopk_w, ws, n_chunks=1):
+    _check(load().moe_layer_bwd_routed(C.byref(cfg), _p(dy), _p(w1), _p(w3), _p(w2), _p(saved), _sz(saved), _p(dx),
+                                       _p(dw1), _p(dw3), _p(dw2), _p(dtopk_w), _p(ws), _sz(ws), C.c_int32(n_chunks),
+                                       _stream()))

@@ -308,9 +308,10 @@ moe_status_t moe_route_bwd(const moe_config_t* cfg, const void* x, const void* w
 static moe_status_t layer_fwd_impl(const char* fn, const moe_config_t* cfg, const void* x, const void* w_gate,
                                    const float* b_gate, const void* w1, const void* w3, const void* w2, void* y,
                                    void* saved, size_t saved_bytes, void* workspace, size_t workspace_bytes_, int r,
-                                   void* stream, void* aux_stream) {
+                                   void* stream, void* aux_stream, bool routed = false) {
   CHECK_CFG(cfg);
-  NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(w1); NOT_NULL(w2); NOT_NULL(y); NOT_NULL(saved);
+  NOT_NULL(x); NOT_NULL(w1); NOT_NULL(w2); NOT_NULL(y); NOT_NULL(saved);
+  if (!routed) NOT_NULL(w_gate);
   if (cfg->act == MOE_ACT_SWIGLU) NOT_NULL(w3);
   REQUIRE(r >= 1 && r <= MOE_MAX_CHUNKS, MOE_ERR_INVALID_ARG, "%s: %d chunks, must be 1..%d", fn, r, MOE_MAX_CHUNKS);
   CHECK_WS(cfg, workspace, workspace_bytes_);
@@ -321,12 +322,14 @@ static moe_status_t layer_fwd_impl(const char* fn, const moe_config_t* cfg, cons
   hipStream_t s = as_stream(stream);
   void* a3 = cfg->act == MOE_ACT_SWIGLU ? at(MOE_SAVED_A3) : nullptr;
   const int32_t* offsets = (const int32_t*)at(MOE_SAVED_OFFSETS);
-  moe_status_t st = launch_route(*cfg, x, w_gate, b_gate, (float*)at(MOE_SAVED_LOGITS), (float*)at(MOE_SAVED_PROBS),
-                                 (int32_t*)at(MOE_SAVED_TOPK_IDX), (float*)at(MOE_SAVED_TOPK_W),
-                                 (int32_t*)at(MOE_SAVED_POS), (int32_t*)at(MOE_SAVED_ROW_OF),
-                                 (int32_t*)at(MOE_SAVED_COUNT), (int32_t*)at(MOE_SAVED_OFFSETS),
-                                 (int32_t*)at(MOE_SAVED_SRC_OF_ROW), workspace, s);
-  if (st != MOE_OK) return st;
+  moe_status_t st = MOE_OK;
+  if (!routed) {  // routed: a moe_route* call has already written the routing tensors of `saved`
+    st = launch_route(*cfg, x, w_gate, b_gate, (float*)at(MOE_SAVED_LOGITS), (float*)at(MOE_SAVED_PROBS),
+                      (int32_t*)at(MOE_SAVED_TOPK_IDX), (float*)at(MOE_SAVED_TOPK_W), (int32_t*)at(MOE_SAVED_POS),
+                      (int32_t*)at(MOE_SAVED_ROW_OF), (int32_t*)at(MOE_SAVED_COUNT), (int32_t*)at(MOE_SAVED_OFFSETS),
+                      (int32_t*)at(MOE_SAVED_SRC_OF_ROW), workspace, s);
+    if (st != MOE_OK) return st;
+  }
   if (r == 1) {
     st = launch_dispatch(*cfg, x, (const int32_t*)at(MOE_SAVED_ROW_OF), at(MOE_SAVED_XE), s);
     if (st != MOE_OK) return st;
@@ -394,10 +397,14 @@ moe_status_t moe_layer_fwd_chunked(const moe_config_t* cfg, const void* x, const
 static moe_status_t layer_bwd_impl(const char* fn, const moe_config_t* cfg, const void* dy, const void* x,
                                    const void* w_gate, const void* w1, const void* w3, const void* w2, const void* saved,
                                    size_t saved_bytes, void* dx, void* dw_gate, float* db_gate, void* dw1, void* dw3,
-                                   void* dw2, void* workspace, size_t workspace_bytes_, int r, void* stream) {
+                                   void* dw2, void* workspace, size_t workspace_bytes_, int r, void* stream,
+                                   float* dtopk_w_out = nullptr) {
+  // dtopk_w_out: stop before the gate (its backward is the caller's next call) and leave the gradient of the
+  // gate weights there
+  const bool routed = dtopk_w_out != nullptr;
   CHECK_CFG(cfg);
-  NOT_NULL(dy); NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(w1); NOT_NULL(w2); NOT_NULL(saved); NOT_NULL(dx);
-  NOT_NULL(dw_gate); NOT_NULL(dw1); NOT_NULL(dw2);
+  NOT_NULL(dy); NOT_NULL(w1); NOT_NULL(w2); NOT_NULL(saved); NOT_NULL(dx); NOT_NULL(dw1); NOT_NULL(dw2);
+  if (!routed) { NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(dw_gate); }
   if (cfg->act == MOE_ACT_SWIGLU) { NOT_NULL(w3); NOT_NULL(dw3); }
   REQUIRE(r >= 1 && r <= MOE_MAX_CHUNKS, MOE_ERR_INVALID_ARG, "%s: %d chunks, must be 1..%d", fn, r, MOE_MAX_CHUNKS);
   CHECK_WS(cfg, workspace, workspace_bytes_);
@@ -409,7 +416,7 @@ static moe_status_t layer_bwd_impl(const char* fn, const moe_config_t* cfg, cons
   unsigned char* w = static_cast<unsigned char*>(workspace);
   void* dq = w + bp.off_dq;
   void* dxe = w + bp.off_dxe;
-  float* dtw = reinterpret_cast<float*>(w + bp.off_dtw);
+  float* dtw = routed ? dtopk_w_out : reinterpret_cast<float*>(w + bp.off_dtw);
   hipStream_t s = as_stream(stream);
   const int32_t* row_of = (const int32_t*)at(MOE_SAVED_ROW_OF);
   const int32_t* offsets = (const int32_t*)at(MOE_SAVED_OFFSETS);
@@ -437,7 +444,7 @@ static moe_status_t layer_bwd_impl(const char* fn, const moe_config_t* cfg, cons
     if (st != MOE_OK) return st;
   }
   st = launch_dispatch_bwd(*cfg, dxe, row_of, dy, dx, s);
-  if (st != MOE_OK) return st;
+  if (st != MOE_OK || routed) return st;
   return launch_route_bwd(*cfg, x, w_gate, (const float*)at(MOE_SAVED_PROBS), (const int32_t*)at(MOE_SAVED_TOPK_IDX),
                           (const int32_t*)at(MOE_SAVED_POS), dtw, dw_gate, db_gate, dx, w + bp.off_route, s);
 }
@@ -456,6 +463,22 @@ moe_status_t moe_layer_bwd_chunked(const moe_config_t* cfg, const void* dy, cons
                                    void* workspace, size_t workspace_bytes_, int32_t n_chunks, void* stream) {
   return layer_bwd_impl("moe_layer_bwd_chunked", cfg, dy, x, w_gate, w1, w3, w2, saved, saved_bytes, dx, dw_gate, db_gate,
                         dw1, dw3, dw2, workspace, workspace_bytes_, n_chunks, stream);
+}
+
+moe_status_t moe_layer_fwd_routed(const moe_config_t* cfg, const void* x, const void* w1, const void* w3, const void* w2,
+                                  void* y, void* saved, size_t saved_bytes, void* workspace, size_t workspace_bytes_,
+                                  int32_t n_chunks, void* stream, void* aux_stream) {
+  return layer_fwd_impl("moe_layer_fwd_routed", cfg, x, nullptr, nullptr, w1, w3, w2, y, saved, saved_bytes, workspace,
+                        workspace_bytes_, n_chunks, stream, aux_stream, true);
+}
+
+moe_status_t moe_layer_bwd_routed(const moe_config_t* cfg, const void* dy, const void* w1, const void* w3, const void* w2,
+                                  const void* saved, size_t saved_bytes, void* dx, void* dw1, void* dw3, void* dw2,
+                                  float* dtopk_w, void* workspace, size_t workspace_bytes_, int32_t n_chunks,
+                                  void* stream) {
+  REQUIRE(dtopk_w != nullptr, MOE_ERR_INVALID_ARG, "moe_layer_bwd_routed: argument 'dtopk_w' is NULL");
+  return layer_bwd_impl("moe_layer_bwd_routed", cfg, dy, nullptr, nullptr, w1, w3, w2, saved, saved_bytes, dx, nullptr,
+                        nullptr, dw1, dw3, dw2, workspace, workspace_bytes_, n_chunks, stream, dtopk_w);
 }
 
 const char* moe_last_error(void) { return moe::g_err; }

@@ -1,0 +1,121 @@
+"""The layer after the gate (moe_layer_fwd_routed / moe_layer_bwd_routed) through the C ABI.
+
+With moe_route before and moe_route_bwd after, every output and every saved tensor must be bit-identical to
+the fused moe_layer_fwd / moe_layer_bwd (which the other GPU tests hold against the oracle); with the X-MoE
+gate the same calls are held against the oracle's chain of functions."""
+import numpy as np
+import pytest
+import torch
+
+import moe_synth as S
+import paper_2501_10714_amd as moe
+from moe_harness import TOL, Buffers, cap_of, dev_inputs, make_cfg, rel_err, run_layer, to_dev, to_np
+from oracle import moe_oracle as O
+from test_gpu_parity import CASES
+from test_gpu_xmoe_gate import CASES as XCASES
+
+pytestmark = pytest.mark.gpu
+
+ROUTING_VIEWS = [("logits", torch.float32), ("probs", torch.float32), ("topk_idx", torch.int32), ("topk_w", torch.float32),
+                 ("pos", torch.int32), ("row_of", torch.int32), ("count", torch.int32), ("offsets", torch.int32),
+                 ("src_of_row", torch.int32)]
+
+
+def routing_views(cfg, saved):
+    return {n: moe.saved_view(cfg, saved, n, dt) for n, dt in ROUTING_VIEWS}
+
+
+def same_bits(a, b):
+    return torch.equal(a.contiguous().view(torch.uint8), b.contiguous().view(torch.uint8))
+
+
+@pytest.mark.parametrize("name,r", [("tiny_full", 1), ("mixtral_small", 1), ("fine_small", 2), ("switch_small", 3),
+                                    ("sigmoid_glu", 1), ("expert_choice_glu", 2), ("f32_ragged", 1)])
+def test_routed_layer_is_bit_identical_to_the_fused_layer(name, r):
+    w = CASES[name]
+    d = S.draw_all(w)
+    dd = dev_inputs(d)
+    cfg, ref = run_layer(w, d, dd=dd)
+    b = Buffers(w, cfg)
+    b.saved.fill_(0x7B); b.y.fill_(1); b.dx.fill_(1); b.dw1.fill_(1); b.dw2.fill_(1); b.dw_gate.fill_(1)
+    if b.dw3 is not None:
+        b.dw3.fill_(1)
+    v = routing_views(cfg, b.saved)
+    moe.moe_route(cfg, dd["x"], dd["w_gate"], dd["b_gate"], v["logits"], v["probs"], v["topk_idx"], v["topk_w"], v["pos"],
+                  v["row_of"], v["count"], v["offsets"], v["src_of_row"], b.ws)
+    aux = torch.cuda.Stream() if r > 1 else None
+    moe.moe_layer_fwd_routed(cfg, dd["x"], dd["w1"], dd["w3"], dd["w2"], b.y, b.saved, b.ws, r, aux)
+    moe.moe_layer_bwd_routed(cfg, dd["dy"], dd["w1"], dd["w3"], dd["w2"], b.saved, b.dx, b.dw1, b.dw3, b.dw2, b.dtopk_w,
+                             b.ws, r)
+    has_bias = d["b_gate"] is not None
+    moe.moe_route_bwd(cfg, dd["x"], dd["w_gate"], v["probs"], v["topk_idx"], v["pos"], b.dtopk_w, b.dw_gate,
+                      b.db_gate if has_bias else None, b.dx, b.ws)
+    torch.cuda.synchronize()
+    A = int(moe.saved_view(cfg, ref.saved, "offsets", torch.int32)[-1])
+    for n, dt in ROUTING_VIEWS:
+        assert same_bits(moe.saved_view(cfg, b.saved, n, dt), moe.saved_view(cfg, ref.saved, n, dt)), n
+    for n, width in (("xe", w.M), ("q", w.M), ("a1", w.H), ("hh", w.H)) + ((("a3", w.H),) if w.gated else ()):
+        dt = torch.bfloat16 if w.dtype == S.DT_BF16 else torch.float32
+        got = moe.saved_view(cfg, b.saved, n, dt)[:A * width]
+        want = moe.saved_view(cfg, ref.saved, n, dt)[:A * width]
+        assert same_bits(got, want), n
+    for n in ("y", "dx", "dw1", "dw2", "dw_gate") + (("dw3",) if w.gated else ()) + (("db_gate",) if has_bias else ()):
+        assert same_bits(getattr(b, n), getattr(ref, n)), n
+
+
+@pytest.mark.parametrize("name,r", [("xmoe_bf16_topk", 1), ("xmoe_bf16_drops", 3), ("xmoe_f32_sigmoid", 2)])
+def test_xmoe_layer_through_the_routed_calls(name, r):
+    """X-MoE gate -> moe_layer_fwd_routed -> moe_layer_bwd_routed -> X-MoE gate backward, against the oracle."""
+    w, dproj = XCASES[name]
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    f = lambda a: None if a is None else S.to_f64(a)
+    x, wp, wg = S.draw_x(w), S.draw_w_proj(w, dproj), S.draw_w_embed(w, dproj)
+    dw = S.draw_all(w)
+    w1, w3, w2, dy = dw["w1"], dw["w3"], dw["w2"], dw["dy"]
+    ro = O.route_xmoe(f(x), f(wp), f(wg), w.k, cap_of(w), w.renormalize)
+    xe = O.order(f(x), ro["row_of"], int(ro["offsets"][-1]))
+    q, saved = O.expert_ffn(xe, ro["offsets"], f(w1), f(w3), f(w2), w.act)
+    y = O.inverse_order(q, ro["topk_w"], ro["row_of"], f(x) if w.add_residual else None)
+    dq, dtw = O.inverse_order_bwd(f(dy), q, ro["topk_w"], ro["row_of"])
+    dxe, dw1, dw3, dw2 = O.expert_ffn_bwd(dq, xe, ro["offsets"], f(w1), f(w3), f(w2), saved, w.act)
+    dx = O.order_bwd(dxe, ro["row_of"], f(dy) if w.add_residual else None)
+    _, dwp, dwg, dx_gate = O.gate_bwd_xmoe(f(x), f(wp), f(wg), ro["proj"], ro["logits"], ro["topk_idx"], ro["pos"], dtw,
+                                           w.renormalize)
+
+    ws_x = torch.empty(moe.moe_route_xmoe_workspace_bytes(cfg, dproj), dtype=torch.uint8, device="cuda")
+    proj = torch.empty(w.N, dproj, dtype=torch.float32, device="cuda")
+    xd, wpd, wgd, w1d, w3d, w2d, dyd = (None if a is None else to_dev(a) for a in (x, wp, wg, w1, w3, w2, dy))
+    v = routing_views(cfg, b.saved)
+    moe.moe_route_xmoe(cfg, xd, wpd, wgd, dproj, proj, v["logits"], v["probs"], v["topk_idx"], v["topk_w"], v["pos"],
+                       v["row_of"], v["count"], v["offsets"], v["src_of_row"], ws_x)
+    aux = torch.cuda.Stream() if r > 1 else None
+    moe.moe_layer_fwd_routed(cfg, xd, w1d, w3d, w2d, b.y, b.saved, b.ws, r, aux)
+    moe.moe_layer_bwd_routed(cfg, dyd, w1d, w3d, w2d, b.saved, b.dx, b.dw1, b.dw3, b.dw2, b.dtopk_w, b.ws, r)
+    dw_proj = torch.empty(w.M, dproj, dtype=b.dw_gate.dtype, device="cuda")
+    dw_gate = torch.empty(dproj, w.E, dtype=b.dw_gate.dtype, device="cuda")
+    moe.moe_route_xmoe_bwd(cfg, xd, wpd, wgd, dproj, proj, v["probs"], v["topk_idx"], v["pos"], b.dtopk_w, dw_proj, dw_gate,
+                           b.dx, ws_x)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(v["row_of"]).reshape(w.N, w.k), ro["row_of"])
+    tol = TOL[w.dtype]
+    assert rel_err(to_np(b.y), y) <= tol
+    assert rel_err(to_np(b.dtopk_w), dtw) <= tol
+    assert rel_err(to_np(b.dx), dx + dx_gate) <= tol
+    assert rel_err(to_np(dw_proj), dwp) <= tol
+    assert rel_err(to_np(dw_gate), dwg) <= tol
+    assert rel_err(to_np(b.dw1), dw1) <= tol
+    assert rel_err(to_np(b.dw2), dw2) <= tol
+    if w.gated:
+        assert rel_err(to_np(b.dw3), dw3) <= tol
+
+
+def test_routed_calls_check_their_arguments():
+    w = CASES["tiny_full"]
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    dd = dev_inputs(S.draw_all(w))
+    with pytest.raises(moe.MoeError, match="dtopk_w"):
+        moe.moe_layer_bwd_routed(cfg, dd["dy"], dd["w1"], dd["w3"], dd["w2"], b.saved, b.dx, b.dw1, b.dw3, b.dw2, None, b.ws)
+    with pytest.raises(moe.MoeError, match="chunks"):
+        moe.moe_layer_fwd_routed(cfg, dd["x"], dd["w1"], dd["w3"], dd["w2"], b.y, b.saved, b.ws, 0)
