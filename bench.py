@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--fit-expert-model", action="store_true",
                     help="time the expert FFN on 1/r of the rows of every expert, r = 1, 2, 4, 8, 16, and fit the linear model "
                          "t = alpha + (n / r) * beta of FSMoE Sec. 4.1; reports the fit and what Algorithm 1 picks on one GPU")
+    ap.add_argument("--gates", action="store_true",
+                    help="also time a layer step with each of the other gates of FSMoE Sec. 2.1 at the same shape (sigmoid, noisy, "
+                         "X-MoE with a 256-wide projection, expert choice with the same number of expert rows); reported "
+                         "beside the headline figure, the counterpart on one GPU of the paper's comparison of gates (Table 6)")
     ap.add_argument("--calibrate-gemm", action="store_true",
                     help="also time the vendor library's plain bf16 GEMM (torch.matmul) for about a second per layout on this box: "
                          "context for the MFMA roofline fraction, since the sustained clock differs from box to box")
@@ -248,6 +252,9 @@ def main():
         out["chunked"] = {"n_chunks": args.chunks, "streams": 2, "ms_per_step": round(ms_c, 3),
                           "tokens_per_s": round(w.N / ms_c * 1e3, 1)}
 
+    if args.gates:
+        out["gates"] = time_gates(torch, moe, S, w, d, args, ms_per_step)
+
     if not args.no_breakdown:
         bpe = 2 if w.dtype == S.DT_BF16 else 4
         N, M, E, k = w.N, w.M, w.E, w.k
@@ -276,6 +283,83 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)
+
+
+def time_gates(torch, moe, S, w, d, args, ms_default):
+    """ms per layer step (forward + backward) with each gate of Sec. 2.1, same N, M, H, E and expert weights."""
+    from moe_harness import Buffers, make_cfg
+    dt = d["x"].dtype
+    i32, f32 = torch.int32, torch.float32
+    names = [("logits", f32), ("probs", f32), ("topk_idx", i32), ("topk_w", f32), ("pos", i32), ("row_of", i32),
+             ("count", i32), ("offsets", i32), ("src_of_row", i32)]
+
+    def clock(step):
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        return round((time.perf_counter() - t0) * 1e3 / args.steps, 3)
+
+    res = {"as_configured (renormalize=%d)" % w.renormalize: round(ms_default, 3)}
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    rnd = lambda shape, std: (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std)
+
+    def fused(wl):
+        cfg = make_cfg(wl)
+        b = Buffers(wl, cfg)
+
+        def step():
+            moe.moe_layer_fwd(cfg, d["x"], d["w_gate"], d["b_gate"], d["w1"], d["w3"], d["w2"], b.y, b.saved, b.ws)
+            moe.moe_layer_bwd(cfg, d["dy"], d["x"], d["w_gate"], d["w1"], d["w3"], d["w2"], b.saved, b.dx, b.dw_gate,
+                              b.db_gate if d["b_gate"] is not None else None, b.dw1, b.dw3, b.dw2, b.ws)
+        t = clock(step)
+        del b
+        torch.cuda.empty_cache()
+        return t
+
+    res["sigmoid"] = fused(S.scaled(w, renormalize=2))
+    if w.E <= 8:   # one slot per expert; every expert keeps N k / E tokens: the same number of expert rows
+        res["expert_choice (%d tokens per expert)" % (w.N * w.k // w.E)] = fused(
+            S.scaled(w, k=w.E, f=float(w.k) / w.E, renormalize=3))
+
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    v = {n: moe.saved_view(cfg, b.saved, n, t) for n, t in names}
+    route_out = [v[n] for n, _ in names[1:]]
+    # noisy gate: the draws are an input
+    w_noise = rnd((w.M, w.E), 0.02).to(dt)
+    noise = rnd((w.N, w.E), 1.0)
+    nl = torch.empty(w.N, w.E, dtype=f32, device="cuda")
+    dw_noise = torch.empty_like(b.dw_gate)
+
+    def step_noisy():
+        moe.moe_route_noisy(cfg, d["x"], d["w_gate"], d["b_gate"], w_noise, noise, v["logits"], nl, *route_out, b.ws)
+        moe.moe_layer_fwd_routed(cfg, d["x"], d["w1"], d["w3"], d["w2"], b.y, b.saved, b.ws)
+        moe.moe_layer_bwd_routed(cfg, d["dy"], d["w1"], d["w3"], d["w2"], b.saved, b.dx, b.dw1, b.dw3, b.dw2, b.dtopk_w, b.ws)
+        moe.moe_route_noisy_bwd(cfg, d["x"], d["w_gate"], w_noise, noise, nl, v["probs"], v["topk_idx"], v["pos"], b.dtopk_w,
+                                b.dw_gate, b.db_gate if d["b_gate"] is not None else None, dw_noise, b.dx, b.ws)
+    res["noisy"] = clock(step_noisy)
+    # X-MoE: 256-wide projection, cosine scores
+    dp = 256
+    w_proj = rnd((w.M, dp), 0.02).to(dt)
+    w_emb = rnd((dp, w.E), 0.5).to(dt)
+    proj = torch.empty(w.N, dp, dtype=f32, device="cuda")
+    ws_x = torch.empty(moe.moe_route_xmoe_workspace_bytes(cfg, dp), dtype=torch.uint8, device="cuda")
+    dw_proj = torch.empty(w.M, dp, dtype=dt, device="cuda")
+    dw_emb = torch.empty(dp, w.E, dtype=dt, device="cuda")
+
+    def step_xmoe():
+        moe.moe_route_xmoe(cfg, d["x"], w_proj, w_emb, dp, proj, v["logits"], *route_out, ws_x)
+        moe.moe_layer_fwd_routed(cfg, d["x"], d["w1"], d["w3"], d["w2"], b.y, b.saved, b.ws)
+        moe.moe_layer_bwd_routed(cfg, d["dy"], d["w1"], d["w3"], d["w2"], b.saved, b.dx, b.dw1, b.dw3, b.dw2, b.dtopk_w, b.ws)
+        moe.moe_route_xmoe_bwd(cfg, d["x"], w_proj, w_emb, dp, proj, v["probs"], v["topk_idx"], v["pos"], b.dtopk_w, dw_proj,
+                               dw_emb, b.dx, ws_x)
+    res["xmoe (d_proj=%d)" % dp] = clock(step_xmoe)
+    return res
 
 
 def cpu_baseline(w):
