@@ -14,6 +14,8 @@
 //
 // The logits are an fp64 GEMM on the vector ALU (register tiled, operands through LDS): the price of
 // routing that matches an independent oracle bit for bit whatever the summation order.
+#include <stdlib.h>
+
 #include "common.h"
 #include "gemm_params.h"
 
@@ -93,6 +95,92 @@ template <> struct Widen<float> {
     d[2] = (double)__uint_as_float(r.z); d[3] = (double)__uint_as_float(r.w);
   }
 };
+
+// Everything after the product, for the tile of 64 tokens whose logits are in lg (or, mode kGateFromLogits, in
+// memory): logits out, top-k and G(I) (one token per lane of wave 0), the histogram of choices.  Called by all
+// threads of the block; hcnt has been cleared and lg written before the call (with a barrier in between).
+__device__ __forceinline__ void gate_tail(float* __restrict__ lg, int32_t* __restrict__ hcnt, float* __restrict__ logits,
+                                          float* __restrict__ probs, int32_t* __restrict__ topk_idx,
+                                          float* __restrict__ topk_w, int32_t* __restrict__ hist, int n_tokens,
+                                          int n_experts, int top_k, int renormalize, int nb, int mode, int nthreads) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int t0 = blockIdx.x * kTile;
+  const int lgs = n_experts + 1;
+  if (mode == kGateFromLogits) {  // the tile's logits come from memory
+    for (int i = tid; i < kTile * n_experts; i += nthreads) {
+      int tk = i / n_experts, e = i % n_experts;
+      lg[tk * lgs + e] = t0 + tk < n_tokens ? logits[(size_t)(t0 + tk) * n_experts + e] : 0.0f;
+    }
+    __syncthreads();
+  } else {  // logits out, coalesced over the tile
+    for (int i = tid; i < kTile * n_experts; i += nthreads) {
+      int tk = i / n_experts, e = i % n_experts;
+      if (t0 + tk < n_tokens) logits[(size_t)(t0 + tk) * n_experts + e] = lg[tk * lgs + e];
+    }
+    if (mode == kGateLogitsOnly) return;
+  }
+
+  // top-k and G(I): one token per lane of wave 0
+  if (wave == 0) {
+    const int t = t0 + lane;
+    if (t < n_tokens) {
+      float* l = lg + lane * lgs;
+      int sel[kMaxK];
+      float selv[kMaxK];
+      float prev_v = 0.0f;
+      int prev_e = -1;
+      for (int j = 0; j < top_k; ++j) {
+        float bv = 0.0f;
+        int be = -1;
+        for (int e = 0; e < n_experts; ++e) {
+          float v = l[e];
+          bool eligible = (j == 0) || (v < prev_v) || (v == prev_v && e > prev_e);
+          if (eligible && (be < 0 || v > bv)) { bv = v; be = e; }
+        }
+        if (be < 0) {  // only with NaN logits (every comparison false): lowest expert not yet taken, so indices stay valid
+          for (int e = 0; e < n_experts && be < 0; ++e) {
+            bool taken = false;
+            for (int i = 0; i < j; ++i) taken |= sel[i] == e;
+            if (!taken) { be = e; bv = l[e]; }
+          }
+        }
+        sel[j] = be; selv[j] = bv; prev_v = bv; prev_e = be;
+        topk_idx[(size_t)t * top_k + j] = be;
+        atomicAdd(&hcnt[j * n_experts + be], 1);
+      }
+      const float mx = selv[0];
+      if (renormalize == MOE_GATE_SIGMOID) {  // sigmoid gate: sigma(H_i), the choices do not interact
+        for (int e = 0; e < n_experts; ++e) l[e] = 1.0f / (1.0f + expf(-l[e]));
+        for (int j = 0; j < top_k; ++j) topk_w[(size_t)t * top_k + j] = l[sel[j]];
+      } else if (renormalize) {
+        float z[kMaxK], s = 0.0f;
+        for (int j = 0; j < top_k; ++j) { z[j] = expf(selv[j] - mx); s += z[j]; }
+        for (int e = 0; e < n_experts; ++e) l[e] = 0.0f;
+        for (int j = 0; j < top_k; ++j) {
+          float w = z[j] / s;
+          l[sel[j]] = w;
+          topk_w[(size_t)t * top_k + j] = w;
+        }
+      } else {
+        float s = 0.0f;
+        for (int e = 0; e < n_experts; ++e) { float z = expf(l[e] - mx); l[e] = z; s += z; }
+        for (int e = 0; e < n_experts; ++e) l[e] = l[e] / s;
+        for (int j = 0; j < top_k; ++j) topk_w[(size_t)t * top_k + j] = l[sel[j]];
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < kTile * n_experts; i += nthreads) {
+    int tk = i / n_experts, e = i % n_experts;
+    if (t0 + tk < n_tokens) probs[(size_t)(t0 + tk) * n_experts + e] = lg[tk * lgs + e];
+  }
+  for (int i = tid; i < top_k * n_experts; i += nthreads) {
+    int j = i / n_experts, e = i % n_experts;
+    hist[((size_t)e * top_k + j) * nb + blockIdx.x] = hcnt[i];
+  }
+}
 
 // logits = fp32(x.W_g + b_g) with the products and the sum in fp64, then top-k, G(I) and the
 // histogram of choices, for one tile of 64 tokens.  The fp64 GEMM is register tiled: a thread owns
@@ -241,78 +329,151 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
     __syncthreads();
   }
 
-  if (mode == kGateFromLogits) {  // the tile's logits come from memory
-    for (int i = tid; i < kTile * n_experts; i += kGateThreads) {
-      int tk = i / n_experts, e = i % n_experts;
-      lg[tk * lgs + e] = t0 + tk < n_tokens ? logits[(size_t)(t0 + tk) * n_experts + e] : 0.0f;
-    }
-    __syncthreads();
-  } else {  // logits out, coalesced over the tile
-    for (int i = tid; i < kTile * n_experts; i += kGateThreads) {
-      int tk = i / n_experts, e = i % n_experts;
-      if (t0 + tk < n_tokens) logits[(size_t)(t0 + tk) * n_experts + e] = lg[tk * lgs + e];
-    }
-    if (mode == kGateLogitsOnly) return;
-  }
+  gate_tail(lg, hcnt, logits, probs, topk_idx, topk_w, hist, n_tokens, n_experts, top_k, renormalize, nb, mode, kGateThreads);
+}
 
-  // top-k and G(I): one token per lane of wave 0
-  if (wave == 0) {
-    const int t = t0 + lane;
-    if (t < n_tokens) {
-      float* l = lg + lane * lgs;
-      int sel[kMaxK];
-      float selv[kMaxK];
-      float prev_v = 0.0f;
-      int prev_e = -1;
-      for (int j = 0; j < top_k; ++j) {
-        float bv = 0.0f;
-        int be = -1;
-        for (int e = 0; e < n_experts; ++e) {
-          float v = l[e];
-          bool eligible = (j == 0) || (v < prev_v) || (v == prev_v && e > prev_e);
-          if (eligible && (be < 0 || v > bv)) { bv = v; be = e; }
-        }
-        if (be < 0) {  // only with NaN logits (every comparison false): lowest expert not yet taken, so indices stay valid
-          for (int e = 0; e < n_experts && be < 0; ++e) {
-            bool taken = false;
-            for (int i = 0; i < j; ++i) taken |= sel[i] == e;
-            if (!taken) { be = e; bv = l[e]; }
-          }
-        }
-        sel[j] = be; selv[j] = bv; prev_v = bv; prev_e = be;
-        topk_idx[(size_t)t * top_k + j] = be;
-        atomicAdd(&hcnt[j * n_experts + be], 1);
-      }
-      const float mx = selv[0];
-      if (renormalize == MOE_GATE_SIGMOID) {  // sigmoid gate: sigma(H_i), the choices do not interact
-        for (int e = 0; e < n_experts; ++e) l[e] = 1.0f / (1.0f + expf(-l[e]));
-        for (int j = 0; j < top_k; ++j) topk_w[(size_t)t * top_k + j] = l[sel[j]];
-      } else if (renormalize) {
-        float z[kMaxK], s = 0.0f;
-        for (int j = 0; j < top_k; ++j) { z[j] = expf(selv[j] - mx); s += z[j]; }
-        for (int e = 0; e < n_experts; ++e) l[e] = 0.0f;
-        for (int j = 0; j < top_k; ++j) {
-          float w = z[j] / s;
-          l[sel[j]] = w;
-          topk_w[(size_t)t * top_k + j] = w;
-        }
-      } else {
-        float s = 0.0f;
-        for (int e = 0; e < n_experts; ++e) { float z = expf(l[e] - mx); l[e] = z; s += z; }
-        for (int e = 0; e < n_experts; ++e) l[e] = l[e] / s;
-        for (int j = 0; j < top_k; ++j) topk_w[(size_t)t * top_k + j] = l[sel[j]];
-      }
+// ---- the product for at most 8 experts.  Every x element then meets all experts in one thread, so x needs no
+// LDS: a wave owns 8 tokens, its lanes own consecutive 16-byte pieces of their rows (64 lanes = 1 KB of every
+// row per step, read straight from memory into registers, one step ahead), and each lane keeps 8 tokens x 8
+// experts of fp64 partial sums over the k it has seen.  W_g sits in LDS in its stored format (M rows of 8
+// experts, zero padded; 16 bytes of padding after every lane's piece, so the 16-byte reads of 16 neighbouring
+// lanes cover all banks) and is widened as it is used.  At the end the 64 partial sums of the 64 lanes are added
+// by a butterfly in which every step halves what a lane holds (fixed order, so runs repeat): lane l ends with
+// the logit of token l / 8, expert l % 8.
+constexpr int kSmallThreads = 512;  // 8 waves x 8 tokens = the 64-token tile of the tail
+constexpr int kSmallE = 8;
+
+template <typename T> struct SmallGate;
+template <> struct SmallGate<bf16_t> {
+  static constexpr int kV = 8;  // k per 16-byte piece of an x row
+  __device__ static __forceinline__ double x_at(const uint4& r, int j) {
+    const uint32_t w = j < 2 ? r.x : j < 4 ? r.y : j < 6 ? r.z : r.w;
+    return (double)__uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16));
+  }
+  // row of 8 experts (16 bytes) -> doubles
+  __device__ static __forceinline__ void w_row(const unsigned char* p, double* d) {
+    Widen<bf16_t>::run(*reinterpret_cast<const uint4*>(p), d);
+  }
+};
+template <> struct SmallGate<float> {
+  static constexpr int kV = 4;
+  __device__ static __forceinline__ double x_at(const uint4& r, int j) {
+    return (double)__uint_as_float(j == 0 ? r.x : j == 1 ? r.y : j == 2 ? r.z : r.w);
+  }
+  __device__ static __forceinline__ void w_row(const unsigned char* p, double* d) {  // 32 bytes
+    Widen<float>::run(*reinterpret_cast<const uint4*>(p), d);
+    Widen<float>::run(*reinterpret_cast<const uint4*>(p + 16), d + 4);
+  }
+};
+constexpr int kSmallPiece = 128 + 16;  // LDS bytes of the W rows of one lane's piece (kV rows of 8 experts) + padding
+
+inline size_t small_gate_lds_bytes(int d_model, int n_experts, int top_k, int v) {
+  const int pieces = ceil_div(d_model, 64 * v) * 64;
+  return (size_t)pieces * kSmallPiece + (size_t)kTile * (n_experts + 1) * sizeof(float) +
+         (size_t)top_k * n_experts * sizeof(int32_t);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kSmallThreads) void gate_small_kernel(
+    const T* __restrict__ x, const T* __restrict__ w_gate, const float* __restrict__ b_gate, float* __restrict__ logits,
+    float* __restrict__ probs, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int32_t* __restrict__ hist,
+    int n_tokens, int d_model, int n_experts, int top_k, int renormalize, int nb, const float* __restrict__ noise,
+    const float* __restrict__ noise_logits, int mode) {
+  typedef SmallGate<T> G;
+  constexpr int V = G::kV;
+  constexpr int kRowBytes = kSmallE * (int)sizeof(T);
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int nsteps = (d_model + 64 * V - 1) / (64 * V);
+  const int pieces = nsteps * 64;
+  unsigned char* wl = smem;                                                   // [pieces][kSmallPiece]
+  float* lg = reinterpret_cast<float*>(wl + (size_t)pieces * kSmallPiece);    // [kTile][n_experts + 1]
+  int32_t* hcnt = reinterpret_cast<int32_t*>(lg + kTile * (n_experts + 1));   // [top_k][n_experts]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lgs = n_experts + 1;
+
+  for (int i = tid; i < top_k * n_experts; i += kSmallThreads) hcnt[i] = 0;
+  // W_g -> LDS: element (k, e) at piece k / V, row k % V, column e; columns past E and rows past M are zero
+  if (n_experts == kSmallE && (reinterpret_cast<uintptr_t>(w_gate) & 15) == 0) {  // whole rows, 16 bytes at a time
+    constexpr int kPer = kRowBytes / 16;  // 16-byte parts of a row
+    for (int i = tid; i < pieces * V * kPer; i += kSmallThreads) {
+      const int k = i / kPer, part = i % kPer;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (k < d_model) v = reinterpret_cast<const uint4*>(w_gate + (size_t)k * kSmallE)[part];
+      *reinterpret_cast<uint4*>(wl + (size_t)(k / V) * kSmallPiece + (k % V) * kRowBytes + part * 16) = v;
+    }
+  } else {
+    for (int i = tid; i < pieces * V * kSmallE; i += kSmallThreads) {
+      const int k = i / kSmallE, e = i % kSmallE;
+      T v = 0;
+      if (k < d_model && e < n_experts) v = w_gate[(size_t)k * n_experts + e];
+      *reinterpret_cast<T*>(wl + (size_t)(k / V) * kSmallPiece + (k % V) * kRowBytes + e * sizeof(T)) = v;
     }
   }
   __syncthreads();
-  for (int i = tid; i < kTile * n_experts; i += kGateThreads) {
-    int tk = i / n_experts, e = i % n_experts;
-    if (t0 + tk < n_tokens) probs[(size_t)(t0 + tk) * n_experts + e] = lg[tk * lgs + e];
+
+  const int tb = blockIdx.x * kTile + wave * 8;  // first token of this wave
+  double acc[8][kSmallE];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int e = 0; e < kSmallE; ++e) acc[i][e] = 0.0;
+  uint4 cur[8], nxt[8];
+  auto fetch = [&](int s, uint4(&r)[8]) {
+    const int k0 = (s * 64 + lane) * V;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      r[i] = (k0 < d_model && tb + i < n_tokens) ? *reinterpret_cast<const uint4*>(x + (size_t)(tb + i) * d_model + k0)
+                                                 : make_uint4(0, 0, 0, 0);
+  };
+  fetch(0, cur);
+  for (int s = 0; s < nsteps; ++s) {
+    if (s + 1 < nsteps) fetch(s + 1, nxt);
+    const unsigned char* wp = wl + (size_t)(s * 64 + lane) * kSmallPiece;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      double wv[kSmallE];
+      G::w_row(wp + j * kRowBytes, wv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const double xv = G::x_at(cur[i], j);
+#pragma unroll
+        for (int e = 0; e < kSmallE; ++e) acc[i][e] = fma(xv, wv[e], acc[i][e]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
   }
-  for (int i = tid; i < top_k * n_experts; i += kGateThreads) {
-    int j = i / n_experts, e = i % n_experts;
-    hist[((size_t)e * top_k + j) * nb + blockIdx.x] = hcnt[i];
+
+  // add the partial sums of the 64 lanes: after the step with distance b a lane holds b of the 64 (token, expert)
+  // sums, those whose index agrees with its lane number in the bits above b
+  double* v = &acc[0][0];
+#pragma unroll
+  for (int b = 32; b >= 1; b >>= 1) {
+    const bool up = (lane & b) != 0;
+#pragma unroll
+    for (int j = 0; j < b; ++j) {
+      const double keep = up ? v[j + b] : v[j];
+      const double send = up ? v[j] : v[j + b];
+      v[j] = keep + __shfl_xor(send, b, 64);
+    }
   }
+  {
+    const int i = lane >> 3, e = lane & 7;
+    if (e < n_experts) {
+      double sum = v[0];
+      if (b_gate != nullptr) sum += (double)b_gate[e];
+      float f = (float)sum;
+      if (noise != nullptr && tb + i < n_tokens) {  // noisy gate, as in gate_topk_kernel
+        const size_t gi = (size_t)(tb + i) * n_experts + e;
+        const double z = (double)noise_logits[gi];
+        const double sp = z > 0.0 ? z + log1p(exp(-z)) : log1p(exp(z));
+        f = (float)((double)f + (double)noise[gi] * sp);
+      }
+      lg[(wave * 8 + i) * lgs + e] = f;
+    }
+  }
+  __syncthreads();
+  gate_tail(lg, hcnt, logits, probs, topk_idx, topk_w, hist, n_tokens, n_experts, top_k, renormalize, nb, mode, kSmallThreads);
 }
 
 // One block per expert: in-place exclusive prefix over its (rank j, tile) histogram entries.
@@ -437,6 +598,21 @@ moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, c
   int32_t* hist = reinterpret_cast<int32_t*>(w + p.off_hist);
   int32_t* total = reinterpret_cast<int32_t*>(w + p.off_total);
   int nwd = p.mpad * p.ep;
+  // at most 8 experts (and W_g fits in LDS): the kernel that reads x straight into registers
+  static const bool force_wide = getenv("MOE_GATE_WIDE") != nullptr;  // for A/B timing of the two gate kernels
+  const size_t small_lds = small_gate_lds_bytes(c.d_model, c.n_experts, c.top_k, SmallGate<T>::kV);
+  if (mode != kGateFromLogits && c.n_experts <= kSmallE && small_lds <= (size_t)160 * 1024 && !force_wide) {
+    static bool attr_set = false;  // LDS above 64 KB must be requested once per kernel
+    if (!attr_set) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gate_small_kernel<T>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(gate_small_kernel<T>, dim3(p.nb), dim3(kSmallThreads), small_lds, s, (const T*)x, (const T*)w_gate,
+                       b_gate, logits, probs, topk_idx, topk_w, hist, c.n_tokens, c.d_model, c.n_experts, c.top_k,
+                       c.renormalize, p.nb, noise, noise_logits, mode);
+    MOE_CHECK_LAUNCH();
+  } else {
   if (mode != kGateFromLogits) {
     hipLaunchKernelGGL(widen_gate_kernel<T>, dim3(ceil_div(nwd, 256)), dim3(256), 0, s, (const T*)w_gate, wd, c.d_model,
                        c.n_experts, p.mpad, p.ep);
@@ -449,6 +625,7 @@ moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, c
     default: launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
   }
   MOE_CHECK_LAUNCH();
+  }
   if (mode == kGateLogitsOnly) return MOE_OK;
   hipLaunchKernelGGL(scan_hist_kernel, dim3(c.n_experts), dim3(256), 0, s, hist, total, c.top_k * p.nb);
   MOE_CHECK_LAUNCH();
@@ -467,6 +644,9 @@ constexpr int kEc = 8;           // experts per register chunk
 
 constexpr int kSplitTokens = 512;  // tokens per split-K group of the bf16 dW_g product
 
+// bf16: the two products of the gate backward go through the MFMA grouped GEMM (fp32: plain kernels)
+inline bool gate_bwd_on_mfma(const moe_config_t& c) { return c.dtype == MOE_BF16; }
+
 struct RouteBwdPlan {
   int ntile;   // 256-token tiles (fp32 path partial sums, and the db_g column sums of both paths)
   int ep;      // experts padded to a multiple of 32 (bf16 path: K of the dx product, N of the dW_g product)
@@ -476,7 +656,7 @@ struct RouteBwdPlan {
 
 RouteBwdPlan route_bwd_plan(const moe_config_t& c) {
   RouteBwdPlan p;
-  const bool bf = c.dtype == MOE_BF16;
+  const bool bf = gate_bwd_on_mfma(c);
   p.ntile = ceil_div(c.n_tokens, kDwTokens);
   p.ep = ceil_div(c.n_experts, 32) * 32;
   p.nsplit = ceil_div(c.n_tokens, kSplitTokens);
@@ -709,12 +889,12 @@ __global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __rest
   }
 }
 
-// fp32: plain FMA kernels.  dW_g through per-256-token partial sums reduced in tile order.
-moe_status_t route_bwd_f32(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
-                           const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
-                           float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
-                           const float* dl_ext, hipStream_t s) {
-  typedef float T;
+// plain FMA kernels (fp32).  dW_g through per-256-token partial sums reduced in tile order.
+template <typename T>
+moe_status_t route_bwd_plain(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
+                             const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                             float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
+                             const float* dl_ext, hipStream_t s) {
   constexpr int V = Elem<T>::kVec;
   RouteBwdPlan p = route_bwd_plan(c);
   unsigned char* w = static_cast<unsigned char*>(ws);
@@ -811,6 +991,20 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
                      (bf16_t*)dw_gate, p.nsplit, c.d_model, c.n_experts, p.ep);
   MOE_CHECK_LAUNCH();
   return MOE_OK;
+}
+
+// the gate's products for dl (own: from probs / dtopk_w; or dl_ext), by dtype and expert count
+moe_status_t route_bwd_any(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
+                           const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
+                           float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
+                           const float* dl_ext, hipStream_t s) {
+  if (gate_bwd_on_mfma(c))
+    return route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, noise, noise_logits, dl_ext, s);
+  if (c.dtype == MOE_BF16)
+    return route_bwd_plain<bf16_t>(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, noise,
+                                   noise_logits, dl_ext, s);
+  return route_bwd_plain<float>(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, noise, noise_logits,
+                                dl_ext, s);
 }
 
 // ----------------------------------------------------------------------------- expert choice (Sec. 2.1)
@@ -1156,10 +1350,7 @@ moe_status_t route_xmoe_bwd_t(const moe_config_t& c, const void* x, const void* 
   MOE_CHECK_LAUNCH();
   // p = I . W_proj: dW_proj = x^T . dp and dx += dp . W_proj^T, the gate's products at width D
   const moe_config_t cd = proj_config(c, d_proj);
-  if (c.dtype == MOE_BF16)
-    return route_bwd_bf16(cd, x, w_proj, nullptr, nullptr, nullptr, nullptr, dw_proj, nullptr, dx, w + p.off_route, nullptr,
-                          nullptr, dp, s);
-  return route_bwd_f32(cd, x, w_proj, nullptr, nullptr, nullptr, nullptr, dw_proj, nullptr, dx, w + p.off_route, nullptr,
+  return route_bwd_any(cd, x, w_proj, nullptr, nullptr, nullptr, nullptr, dw_proj, nullptr, dx, w + p.off_route, nullptr,
                        nullptr, dp, s);
 }
 
@@ -1211,9 +1402,7 @@ moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* 
     MOE_CHECK_LAUNCH();
     dl_ext = dl;
   }
-  return c.dtype == MOE_BF16
-             ? route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, dl_ext, s)
-             : route_bwd_f32(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, dl_ext, s);
+  return route_bwd_any(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, dl_ext, s);
 }
 
 // Backward of the noisy gate: the ordinary gate backward for W_g (dH = dlogits), then the same products for
@@ -1224,10 +1413,7 @@ moe_status_t launch_route_noisy_bwd(const moe_config_t& c, const void* x, const 
                                     float* db_gate, void* dw_noise, void* dx, void* ws, hipStream_t s) {
   moe_status_t st = launch_route_bwd(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s);
   if (st != MOE_OK) return st;
-  return c.dtype == MOE_BF16 ? route_bwd_bf16(c, x, w_noise, probs, topk_idx, pos, dtopk_w, dw_noise, nullptr, dx, ws,
-                                              noise, noise_logits, nullptr, s)
-                             : route_bwd_f32(c, x, w_noise, probs, topk_idx, pos, dtopk_w, dw_noise, nullptr, dx, ws, noise,
-                                             noise_logits, nullptr, s);
+  return route_bwd_any(c, x, w_noise, probs, topk_idx, pos, dtopk_w, dw_noise, nullptr, dx, ws, noise, noise_logits, nullptr, s);
 }
 
 size_t route_xmoe_workspace_bytes(const moe_config_t& c, int d_proj) { return xmoe_plan(c, d_proj).bytes; }
