@@ -273,7 +273,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmP& p, const TileId& t, f
   // The backward epilogues read the saved pre-activations at the output position.  The loads of a
   // 32-row block go out one block ahead (addresses clamped into the tensor, so they need no
   // predicate), and their latency passes under the LDS turn of the block before.
-  constexpr int kNX = EPI == EPI_GLU_BWD ? 2 : EPI == EPI_ACT_BWD ? 1 : 0;
+  constexpr int kNX = EPI == EPI_GLU_BWD ? 2 : (EPI == EPI_ACT_BWD || EPI == EPI_ACCUM) ? 1 : 0;
   u32x4 xin[2][kPasses][kNX > 0 ? kNX : 1];
   auto prefetch = [&](int fm) {
     if constexpr (kNX > 0) {
@@ -284,7 +284,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmP& p, const TileId& t, f
         const long off = out_off(mrow, cc);
 #pragma unroll
         for (int x = 0; x < kNX; ++x)
-          xin[fm & 1][ps][x] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.X[x]) + off));
+          xin[fm & 1][ps][x] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(EPI == EPI_ACCUM ? p.C[0] : p.X[x]) + off));
       }
     }
   };
@@ -346,6 +346,12 @@ __device__ __forceinline__ void tile_epilogue(const GemmP& p, const TileId& t, f
 #pragma unroll
         for (int j = 0; j < 8; ++j) v[j] = siluf_(v[j]) * g[j];
         store8(static_cast<bf16_t*>(p.C[2]) + off, v);
+      } else if (EPI == EPI_ACCUM) {
+        float old[8];
+        widen8(xin[fm & 1][ps][0], old);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] += old[j];
+        store8(static_cast<bf16_t*>(p.C[0]) + off, v);
       } else if (EPI == EPI_ACT_BWD) {
         float a1[8];
         widen8(xin[fm & 1][ps][0], a1);
@@ -930,6 +936,7 @@ moe_status_t launch_gemm_mfma(const GemmP& p, int epi, bool ragged_k, hipStream_
         if (p.act == MOE_ACT_GELU_TANH) return launch_cfg64<TR, EPI_ACT_FWD, MOE_ACT_GELU_TANH>(p, s);
         return launch_cfg64<TR, EPI_ACT_FWD, MOE_ACT_GELU_ERF>(p, s);
       case EPI_GLU_FWD: return launch_cfg64<TR, EPI_GLU_FWD>(p, s);
+      case EPI_ACCUM: return launch_cfg64<KC, EPI_ACCUM>(p, s);
       case EPI_ACT_BWD:
         if (p.act == MOE_ACT_RELU) return launch_cfg64<KC, EPI_ACT_BWD, MOE_ACT_RELU>(p, s);
         if (p.act == MOE_ACT_GELU_TANH) return launch_cfg64<KC, EPI_ACT_BWD, MOE_ACT_GELU_TANH>(p, s);
@@ -945,6 +952,7 @@ moe_status_t launch_gemm_mfma(const GemmP& p, int epi, bool ragged_k, hipStream_
       if (p.act == MOE_ACT_GELU_TANH) return launch_cfg<KC, TR, EPI_ACT_FWD, false, MOE_ACT_GELU_TANH>(p, s);
       return launch_cfg<KC, TR, EPI_ACT_FWD, false, MOE_ACT_GELU_ERF>(p, s);
     case EPI_GLU_FWD: return launch_cfg<KC, TR, EPI_GLU_FWD, false>(p, s);
+    case EPI_ACCUM: return launch_cfg<KC, KC, EPI_ACCUM, false>(p, s);
     case EPI_ACT_BWD:
       if (p.act == MOE_ACT_RELU) return launch_cfg<KC, KC, EPI_ACT_BWD, false, MOE_ACT_RELU>(p, s);
       if (p.act == MOE_ACT_GELU_TANH) return launch_cfg<KC, KC, EPI_ACT_BWD, false, MOE_ACT_GELU_TANH>(p, s);

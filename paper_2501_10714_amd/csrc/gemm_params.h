@@ -13,7 +13,8 @@ enum Epilogue {
   EPI_ACT_FWD = 1,  // C0 = a1 = acc, C2 = hh = act(a1)
   EPI_GLU_FWD = 2,  // two accumulators: C0 = a1, C1 = a3, C2 = hh = silu(a1) * a3
   EPI_ACT_BWD = 3,  // acc = dhh: C0 = da1 = dhh * act'(X0)
-  EPI_GLU_BWD = 4   // acc = dhh: C0 = da1 = dhh * X1 * silu'(X0), C1 = da3 = dhh * silu(X0)
+  EPI_GLU_BWD = 4,  // acc = dhh: C0 = da1 = dhh * X1 * silu'(X0), C1 = da3 = dhh * silu(X0)
+  EPI_ACCUM = 5     // C0 += acc, the old C0 read ahead like the saved activations (bf16 MFMA kernel only)
 };
 
 // Two shapes of raggedness:

@@ -966,8 +966,8 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
     g.A[0] = dlb; g.sAi = p.ep; g.sAk = 1;
     g.B[0] = wgp; g.sBk = 1; g.sBn = p.ep; g.gB = 0;
     g.C[0] = dx; g.ldc = c.d_model; g.N = c.d_model; g.Kfix = p.ep;
-    g.accumulate = 1; g.max_rows = c.n_tokens; g.total_rows_bound = c.n_tokens;
-    moe_status_t st = launch_gemm_mfma(g, EPI_PLAIN, false, s);
+    g.max_rows = c.n_tokens; g.total_rows_bound = c.n_tokens;
+    moe_status_t st = launch_gemm_mfma(g, EPI_ACCUM, false, s);
     if (st != MOE_OK) return st;
   }
   {  // part[g] = x_g^T.dlb_g : [M,rows] x [rows,ep] for every 512-token group
