@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per step of the six expert-GEMM launches at the Mixtral shape, from the rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gg_mfma_kernel_mixtral_hbm_traffic.md (scaled by
 # the factors a plain 1 GiB copy gives: 2.0 and 1.0).  Algorithmic bytes for the same launches: 22.3e9.
-MEASURED_GEMM_TRAFFIC = {"mixtral": {"read": 67.3e9, "written": 8.1e9}}
+MEASURED_GEMM_TRAFFIC = {"mixtral": {"read": 67.8e9, "written": 8.1e9}}
 
 
 def parse():
