@@ -119,3 +119,27 @@ def test_routed_calls_check_their_arguments():
         moe.moe_layer_bwd_routed(cfg, dd["dy"], dd["w1"], dd["w3"], dd["w2"], b.saved, b.dx, b.dw1, b.dw3, b.dw2, None, b.ws)
     with pytest.raises(moe.MoeError, match="chunks"):
         moe.moe_layer_fwd_routed(cfg, dd["x"], dd["w1"], dd["w3"], dd["w2"], b.y, b.saved, b.ws, 0)
+
+
+@pytest.mark.parametrize("name", ["mixtral_small", "fine_small", "switch_small", "expert_choice_glu", "f32_ragged"])
+def test_layer_results_repeat_bit_for_bit(name):
+    """No result depends on the order in which threads or workgroups happen to run (positions come from prefix
+    sums, reductions have a fixed order): two runs on fresh buffers agree in every bit, outputs and saved blob."""
+    w = CASES[name]
+    d = S.draw_all(w)
+    dd = dev_inputs(d)
+    cfg, a = run_layer(w, d, dd=dd)
+    b = Buffers(w, cfg)
+    b.saved.fill_(0x55); b.ws.fill_(0xAA)                     # other leftovers in the scratch memory
+    run_layer(w, d, bufs=b, dd=dd)
+    A = int(moe.saved_view(cfg, a.saved, "offsets", torch.int32)[-1])
+    dt = torch.bfloat16 if w.dtype == S.DT_BF16 else torch.float32
+    for n, t in ROUTING_VIEWS:
+        got, want = moe.saved_view(cfg, b.saved, n, t), moe.saved_view(cfg, a.saved, n, t)
+        if n == "src_of_row":
+            got, want = got[:w.N * w.k], want[:w.N * w.k]
+        assert same_bits(got, want), n
+    for n, width in (("xe", w.M), ("q", w.M), ("a1", w.H), ("hh", w.H)) + ((("a3", w.H),) if w.gated else ()):
+        assert same_bits(moe.saved_view(cfg, b.saved, n, dt)[:A * width], moe.saved_view(cfg, a.saved, n, dt)[:A * width]), n
+    for n in ("y", "dx", "dw1", "dw2", "dw_gate") + (("dw3",) if w.gated else ()) + (("db_gate",) if d["b_gate"] is not None else ()):
+        assert same_bits(getattr(b, n), getattr(a, n)), n
