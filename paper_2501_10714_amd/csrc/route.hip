@@ -332,8 +332,8 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
   gate_tail(lg, hcnt, logits, probs, topk_idx, topk_w, hist, n_tokens, n_experts, top_k, renormalize, nb, mode, kGateThreads);
 }
 
-// ---- the product for at most 8 experts.  Every x element then meets all experts in one thread, so x needs no
-// LDS: a wave owns 8 tokens, its lanes own consecutive 16-byte pieces of their rows (64 lanes = 1 KB of every
+// ---- the product, 8 experts at a time.  Every x element then meets all experts of the group in one thread, so x
+// needs no LDS: a wave owns 8 tokens, its lanes own consecutive 16-byte pieces of their rows (64 lanes = 1 KB of every
 // row per step, read straight from memory into registers, one step ahead), and each lane keeps 8 tokens x 8
 // experts of fp64 partial sums over the k it has seen.  W_g sits in LDS in its stored format (M rows of 8
 // experts, zero padded; 16 bytes of padding after every lane's piece, so the 16-byte reads of 16 neighbouring
@@ -390,75 +390,80 @@ __global__ __launch_bounds__(kSmallThreads) void gate_small_kernel(
   int32_t* hcnt = reinterpret_cast<int32_t*>(lg + kTile * (n_experts + 1));   // [top_k][n_experts]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lgs = n_experts + 1;
+  const int tb = blockIdx.x * kTile + wave * 8;  // first token of this wave
 
   for (int i = tid; i < top_k * n_experts; i += kSmallThreads) hcnt[i] = 0;
-  // W_g -> LDS: element (k, e) at piece k / V, row k % V, column e; columns past E and rows past M are zero
-  if (n_experts == kSmallE && (reinterpret_cast<uintptr_t>(w_gate) & 15) == 0) {  // whole rows, 16 bytes at a time
-    constexpr int kPer = kRowBytes / 16;  // 16-byte parts of a row
-    for (int i = tid; i < pieces * V * kPer; i += kSmallThreads) {
-      const int k = i / kPer, part = i % kPer;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (k < d_model) v = reinterpret_cast<const uint4*>(w_gate + (size_t)k * kSmallE)[part];
-      *reinterpret_cast<uint4*>(wl + (size_t)(k / V) * kSmallPiece + (k % V) * kRowBytes + part * 16) = v;
-    }
-  } else {
-    for (int i = tid; i < pieces * V * kSmallE; i += kSmallThreads) {
-      const int k = i / kSmallE, e = i % kSmallE;
-      T v = 0;
-      if (k < d_model && e < n_experts) v = w_gate[(size_t)k * n_experts + e];
-      *reinterpret_cast<T*>(wl + (size_t)(k / V) * kSmallPiece + (k % V) * kRowBytes + e * sizeof(T)) = v;
-    }
-  }
-  __syncthreads();
 
-  const int tb = blockIdx.x * kTile + wave * 8;  // first token of this wave
-  double acc[8][kSmallE];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int e = 0; e < kSmallE; ++e) acc[i][e] = 0.0;
-  uint4 cur[8], nxt[8];
-  auto fetch = [&](int s, uint4(&r)[8]) {
-    const int k0 = (s * 64 + lane) * V;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      r[i] = (k0 < d_model && tb + i < n_tokens) ? *reinterpret_cast<const uint4*>(x + (size_t)(tb + i) * d_model + k0)
-                                                 : make_uint4(0, 0, 0, 0);
-  };
-  fetch(0, cur);
-  for (int s = 0; s < nsteps; ++s) {
-    if (s + 1 < nsteps) fetch(s + 1, nxt);
-    const unsigned char* wp = wl + (size_t)(s * 64 + lane) * kSmallPiece;
-#pragma unroll
-    for (int j = 0; j < V; ++j) {
-      double wv[kSmallE];
-      G::w_row(wp + j * kRowBytes, wv);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const double xv = G::x_at(cur[i], j);
-#pragma unroll
-        for (int e = 0; e < kSmallE; ++e) acc[i][e] = fma(xv, wv[e], acc[i][e]);
+  // experts in groups of 8; with more than one group the x rows are read again for every group (from L2 or the
+  // memory-side cache: a workgroup's 64 rows are 64 * M elements)
+  for (int e0 = 0; e0 < n_experts; e0 += kSmallE) {
+    const int ge = min(kSmallE, n_experts - e0);  // experts in this group
+    if (e0 > 0) __syncthreads();                  // every wave is done with the W rows of the group before
+    // W_g -> LDS: element (k, e0 + e) at piece k / V, row k % V, column e; columns past the group and rows past M are zero
+    if (ge == kSmallE && n_experts % kSmallE == 0 && (reinterpret_cast<uintptr_t>(w_gate) & 15) == 0) {  // 16 bytes at a time
+      constexpr int kPer = kRowBytes / 16;  // 16-byte parts of a group's share of a row
+      for (int i = tid; i < pieces * V * kPer; i += kSmallThreads) {
+        const int k = i / kPer, part = i % kPer;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (k < d_model) v = reinterpret_cast<const uint4*>(w_gate + (size_t)k * n_experts + e0)[part];
+        *reinterpret_cast<uint4*>(wl + (size_t)(k / V) * kSmallPiece + (k % V) * kRowBytes + part * 16) = v;
+      }
+    } else {
+      for (int i = tid; i < pieces * V * kSmallE; i += kSmallThreads) {
+        const int k = i / kSmallE, e = i % kSmallE;
+        T v = 0;
+        if (k < d_model && e < ge) v = w_gate[(size_t)k * n_experts + e0 + e];
+        *reinterpret_cast<T*>(wl + (size_t)(k / V) * kSmallPiece + (k % V) * kRowBytes + e * sizeof(T)) = v;
       }
     }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
-  }
+    __syncthreads();
 
-  // add the partial sums of the 64 lanes: after the step with distance b a lane holds b of the 64 (token, expert)
-  // sums, those whose index agrees with its lane number in the bits above b
-  double* v = &acc[0][0];
+    double acc[8][kSmallE];
 #pragma unroll
-  for (int b = 32; b >= 1; b >>= 1) {
-    const bool up = (lane & b) != 0;
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < b; ++j) {
-      const double keep = up ? v[j + b] : v[j];
-      const double send = up ? v[j] : v[j + b];
-      v[j] = keep + __shfl_xor(send, b, 64);
+      for (int e = 0; e < kSmallE; ++e) acc[i][e] = 0.0;
+    uint4 cur[8], nxt[8];
+    auto fetch = [&](int s, uint4(&r)[8]) {
+      const int k0 = (s * 64 + lane) * V;
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        r[i] = (k0 < d_model && tb + i < n_tokens) ? *reinterpret_cast<const uint4*>(x + (size_t)(tb + i) * d_model + k0)
+                                                   : make_uint4(0, 0, 0, 0);
+    };
+    fetch(0, cur);
+    for (int s = 0; s < nsteps; ++s) {
+      if (s + 1 < nsteps) fetch(s + 1, nxt);
+      const unsigned char* wp = wl + (size_t)(s * 64 + lane) * kSmallPiece;
+#pragma unroll
+      for (int j = 0; j < V; ++j) {
+        double wv[kSmallE];
+        G::w_row(wp + j * kRowBytes, wv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const double xv = G::x_at(cur[i], j);
+#pragma unroll
+          for (int e = 0; e < kSmallE; ++e) acc[i][e] = fma(xv, wv[e], acc[i][e]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
     }
-  }
-  {
-    const int i = lane >> 3, e = lane & 7;
+
+    // add the partial sums of the 64 lanes: after the step with distance b a lane holds b of the 64 (token, expert)
+    // sums, those whose index agrees with its lane number in the bits above b
+    double* v = &acc[0][0];
+#pragma unroll
+    for (int b = 32; b >= 1; b >>= 1) {
+      const bool up = (lane & b) != 0;
+#pragma unroll
+      for (int j = 0; j < b; ++j) {
+        const double keep = up ? v[j + b] : v[j];
+        const double send = up ? v[j] : v[j + b];
+        v[j] = keep + __shfl_xor(send, b, 64);
+      }
+    }
+    const int i = lane >> 3, e = e0 + (lane & 7);
     if (e < n_experts) {
       double sum = v[0];
       if (b_gate != nullptr) sum += (double)b_gate[e];
@@ -598,10 +603,12 @@ moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, c
   int32_t* hist = reinterpret_cast<int32_t*>(w + p.off_hist);
   int32_t* total = reinterpret_cast<int32_t*>(w + p.off_total);
   int nwd = p.mpad * p.ep;
-  // at most 8 experts (and W_g fits in LDS): the kernel that reads x straight into registers
+  // the kernel that reads x straight into registers, whenever the W_g rows of 8 experts fit in LDS (M up to
+  // about 8000 in bf16); measured faster than gate_topk_kernel at every shape tried (2x at E = 8, 1.1x at 32 and 64,
+  // 1.4x at 256)
   static const bool force_wide = getenv("MOE_GATE_WIDE") != nullptr;  // for A/B timing of the two gate kernels
   const size_t small_lds = small_gate_lds_bytes(c.d_model, c.n_experts, c.top_k, SmallGate<T>::kV);
-  if (mode != kGateFromLogits && c.n_experts <= kSmallE && small_lds <= (size_t)160 * 1024 && !force_wide) {
+  if (mode != kGateFromLogits && small_lds <= (size_t)160 * 1024 && !force_wide) {
     static bool attr_set = false;  // LDS above 64 KB must be requested once per kernel
     if (!attr_set) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gate_small_kernel<T>),

@@ -42,6 +42,9 @@ CASES = {
     # the largest expert count and top-k the library takes: the gate kernel then holds fewer experts per pass
     "experts_256_bf16": S.scaled(W["finegrained"], N=300, M=64, H=64, E=256, k=8, seed=33),
     "experts_130_f32": S.scaled(W["tiny"], N=200, M=40, H=64, E=130, k=8, f=1.5, seed=34),
+    # M so large that the W_g rows of 8 experts do not fit in LDS: the gate kernel that stages x and W_g in chunks
+    "wide_gate_f32": S.scaled(W["tiny"], N=130, M=4608, H=64, E=5, k=2, f=1.5, seed=40),
+    "wide_gate_bf16": S.scaled(W["gpt2"], N=200, M=9216, H=64, E=12, k=2, f=None, seed=41),
     # expert choice (Sec. 2.1): every expert keeps ceil(f N) tokens; one slot per expert, so k = E
     "expert_choice_glu": S.scaled(W["mixtral"], N=2500, M=128, H=192, E=8, k=8, f=0.25, renormalize=3, seed=35),
     "expert_choice_f32": S.scaled(W["tiny"], N=333, M=64, H=96, E=5, k=5, f=0.3, renormalize=3, seed=36),
