@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--fit-expert-model", action="store_true",
                     help="time the expert FFN on 1/r of the rows of every expert, r = 1, 2, 4, 8, 16, and fit the linear model "
                          "t = alpha + (n / r) * beta of FSMoE Sec. 4.1; reports the fit and what Algorithm 1 picks on one GPU")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph that holds moe_layer_fwd + moe_layer_bwd (the calls allocate "
+                         "nothing and never synchronise, so they can be captured); reported beside the headline figure")
     ap.add_argument("--gates", action="store_true",
                     help="also time a layer step with each of the other gates of FSMoE Sec. 2.1 at the same shape (sigmoid, noisy, "
                          "X-MoE with a 256-wide projection, expert choice with the same number of expert rows); reported "
@@ -251,6 +254,20 @@ def main():
         ms_c = (time.perf_counter() - t0) * 1e3 / args.steps
         out["chunked"] = {"n_chunks": args.chunks, "streams": 2, "ms_per_step": round(ms_c, 3),
                           "tokens_per_s": round(w.N / ms_c * 1e3, 1)}
+
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fwd(); bwd()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_g = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["graph"] = {"ms_per_step": round(ms_g, 4), "tokens_per_s": round(w.N / ms_g * 1e3, 1)}
 
     if args.gates:
         out["gates"] = time_gates(torch, moe, S, w, d, args, ms_per_step)
