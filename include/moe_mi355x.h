@@ -10,7 +10,9 @@
  *   - Every tensor pointer is a DEVICE pointer to a dense row-major array owned by the caller.
  *     The library never allocates, frees or keeps device memory and never synchronises: it
  *     enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the default stream)
- *     and returns.  Configuration structs and the size_t* outputs are HOST memory.
+ *     and returns.  Configuration structs and the size_t* outputs are HOST memory.  Tensor pointers,
+ *     the workspace and the saved blob must be 16-byte aligned (rows move as 16-byte vectors);
+ *     a misaligned required pointer is MOE_ERR_INVALID_ARG.
  *   - Activations and weights have the element type cfg->dtype (fp32 or bf16 bit patterns).
  *     Logits, probabilities, gate weights and their gradients are fp32.  Indices are int32.
  *   - A, the number of kept (token, choice) assignments, is data dependent.  Buffers indexed by
@@ -18,7 +20,8 @@
  *     Rows at and beyond A are never read or written.
  *   - Arguments are validated on the host before any launch.  A failed call launches nothing,
  *     returns a status other than MOE_OK and leaves a message for moe_last_error().
- *   - Device data are assumed finite.  Behaviour on NaN/Inf logits is unspecified.
+ *   - Device data are assumed finite.  With NaN/Inf logits the values are unspecified, but the routing
+ *     stays valid (k distinct experts in range per token, consistent counts and index maps).
  *   - Calls that share output or workspace buffers must be ordered by the caller (same stream).
  */
 #ifndef MOE_MI355X_H

@@ -114,7 +114,13 @@ size_t workspace_bytes(const moe_config_t& c) {
 
 inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
 
-#define NOT_NULL(p) REQUIRE((p) != nullptr, MOE_ERR_INVALID_ARG, "%s: argument '%s' is NULL", __func__, #p)
+// a tensor argument: present, and aligned for the 16-byte vector accesses of the kernels
+#define NOT_NULL(p)                                                                                        \
+  do {                                                                                                     \
+    REQUIRE((p) != nullptr, MOE_ERR_INVALID_ARG, "%s: argument '%s' is NULL", __func__, #p);               \
+    REQUIRE((reinterpret_cast<uintptr_t>(p) & 15) == 0, MOE_ERR_INVALID_ARG,                               \
+            "%s: argument '%s' is not 16-byte aligned", __func__, #p);                                     \
+  } while (0)
 #define CHECK_CFG(c)                   \
   do {                                 \
     moe_status_t st__ = check_cfg(c);  \
@@ -209,7 +215,7 @@ static moe_status_t check_xmoe(const char* fn, const moe_config_t* cfg, int32_t 
 
 moe_status_t moe_route_xmoe_workspace_bytes(const moe_config_t* cfg, int32_t d_proj, size_t* ws_bytes) {
   CHECK_CFG(cfg);
-  NOT_NULL(ws_bytes);
+  REQUIRE(ws_bytes != nullptr, MOE_ERR_INVALID_ARG, "moe_route_xmoe_workspace_bytes: argument 'ws_bytes' is NULL");
   REQUIRE(d_proj >= 4 && d_proj <= 256 && d_proj % 4 == 0, MOE_ERR_UNSUPPORTED,
           "moe_route_xmoe_workspace_bytes: d_proj=%d must be a multiple of 4 in 4..256", d_proj);
   *ws_bytes = route_xmoe_workspace_bytes(*cfg, d_proj);
@@ -253,6 +259,7 @@ moe_status_t moe_dispatch_bwd(const moe_config_t* cfg, const void* dxe, const in
   CHECK_CFG(cfg);
   NOT_NULL(dxe); NOT_NULL(row_of); NOT_NULL(dx);
   REQUIRE(!cfg->add_residual || dy != nullptr, MOE_ERR_INVALID_ARG, "moe_dispatch_bwd: add_residual needs dy");
+  if (cfg->add_residual) NOT_NULL(dy);
   return launch_dispatch_bwd(*cfg, dxe, row_of, dy, dx, as_stream(stream));
 }
 
@@ -284,6 +291,7 @@ moe_status_t moe_combine(const moe_config_t* cfg, const void* q, const float* to
   CHECK_CFG(cfg);
   NOT_NULL(q); NOT_NULL(topk_w); NOT_NULL(row_of); NOT_NULL(y);
   REQUIRE(!cfg->add_residual || x != nullptr, MOE_ERR_INVALID_ARG, "moe_combine: add_residual needs x");
+  if (cfg->add_residual) NOT_NULL(x);
   return launch_combine(*cfg, q, topk_w, row_of, x, y, as_stream(stream));
 }
 

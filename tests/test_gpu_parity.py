@@ -340,3 +340,17 @@ def test_nan_logits_still_give_valid_routing():
     for t in range(w.N):
         for j in range(w.k):
             assert row_of[t, j] == offsets[idx[t, j]] + pos[t, j] and src[row_of[t, j]] == t * w.k + j
+
+
+def test_misaligned_tensor_is_rejected():
+    """Rows move as 16-byte vectors: a tensor pointer that is not 16-byte aligned is an argument error, not a fault."""
+    w = CASES["tiny_full"]
+    cfg = make_cfg(w)
+    b = Buffers(w, cfg)
+    d = dev_inputs(S.draw_all(w))
+    x_off = torch.empty(w.N * w.M + 1, dtype=d["x"].dtype, device="cuda")[1:].view(w.N, w.M)   # 4 bytes off
+    with pytest.raises(moe.MoeError, match="16-byte aligned"):
+        moe.moe_dispatch(cfg, x_off, b.row_of, b.xe)
+    with pytest.raises(moe.MoeError, match="16-byte aligned"):
+        moe.moe_route(cfg, x_off, d["w_gate"], None, b.logits, b.probs, b.topk_idx, b.topk_w, b.pos, b.row_of, b.count,
+                      b.offsets, b.src_of_row, b.ws)
