@@ -81,3 +81,37 @@ def test_saved_layout_is_disjoint_and_ordered(lib):
         assert off >= end and off % 256 == 0
         end = off + n
     assert end <= total
+
+
+def test_misaligned_pointers_and_the_new_calls_are_validated_on_the_host(lib):
+    cfg = moe.MoeConfig.make(64, 64, 4, 128, 2, 0, moe.DT_F32, moe.ACT_RELU)
+    null, fake, odd = C.c_void_p(0), C.c_void_p(4096), C.c_void_p(4100)
+    st = lib.moe_dispatch(C.byref(cfg), odd, fake, fake, null)
+    assert st == 1 and "16-byte aligned" in moe.moe_last_error()
+    # the layer after the gate: dtopk_w is required, the chunk count is checked
+    st = lib.moe_layer_bwd_routed(C.byref(cfg), fake, fake, null, fake, fake, C.c_size_t(1 << 30), fake, fake, null, fake,
+                                  null, fake, C.c_size_t(1 << 30), C.c_int32(1), null)
+    assert st == 1 and "dtopk_w" in moe.moe_last_error()
+    st = lib.moe_layer_fwd_routed(C.byref(cfg), fake, fake, null, fake, fake, fake, C.c_size_t(1 << 30), fake,
+                                  C.c_size_t(1 << 30), C.c_int32(99), null, null)
+    assert st == 1 and "chunks" in moe.moe_last_error()
+    # expert choice: one slot per expert and a positive number of tokens per expert
+    with pytest.raises(moe.MoeError, match="expert choice"):
+        moe.moe_workspace_bytes(moe.MoeConfig.make(64, 64, 4, 128, 2, 8, moe.DT_F32, moe.ACT_RELU, 3))
+    with pytest.raises(moe.MoeError, match="expert choice"):
+        moe.moe_workspace_bytes(moe.MoeConfig.make(64, 64, 4, 128, 4, 0, moe.DT_F32, moe.ACT_RELU, 3))
+    ws, _ = moe.moe_workspace_bytes(moe.MoeConfig.make(64, 64, 4, 128, 4, 16, moe.DT_F32, moe.ACT_RELU, 3))
+    assert ws > 0
+    # X-MoE: projection width
+    for d_proj in (0, 6, 260):
+        with pytest.raises(moe.MoeError, match="d_proj"):
+            moe.moe_route_xmoe_workspace_bytes(cfg, d_proj)
+    assert moe.moe_route_xmoe_workspace_bytes(cfg, 32) > 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one-GPU" in r.stderr and r.stdout.strip() == ""
