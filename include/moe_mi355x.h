@@ -23,6 +23,17 @@
  *   - Device data are assumed finite.  With NaN/Inf logits the values are unspecified, but the routing
  *     stays valid (k distinct experts in range per token, consistent counts and index maps).
  *   - Calls that share output or workspace buffers must be ordered by the caller (same stream).
+ *   - Stream capture: no call records a memset, allocates or synchronises, so calls can be captured into a
+ *     HIP graph.  The first gate call on each device makes one host-side hipFuncSetAttribute call (it lifts
+ *     the 64 KB limit on the LDS of the gate kernels; per device, thread-safe, MOE_ERR_DEVICE if the runtime
+ *     refuses it): make one eager call per device before capturing.  The chunked calls with an aux_stream
+ *     create and destroy n_chunks + 1 events per call (host cost of a few microseconds each).
+ *   - Expert rows given by the caller (moe_expert_ffn_fwd/bwd, moe_layer_*_routed with a gate of the caller's):
+ *     offsets must be non-decreasing with offsets[0] = 0, no expert may hold more than min(N, capacity) rows
+ *     (capacity <= 0: N), and offsets[E] <= N*k.  The launch grids are sized from these bounds on the host;
+ *     rows beyond them would silently stay uncomputed.
+ *   - Diagnostics: with MOE_FORCE_PLAIN_GEMM=1 in the environment (read at every expert-FFN call) every
+ *     expert product runs on the plain FMA kernel instead of the MFMA kernel; for A/B checks only.
  */
 #ifndef MOE_MI355X_H
 #define MOE_MI355X_H

@@ -926,7 +926,11 @@ bool gemm_mfma_supported(const GemmP& p, int dtype, int epi, bool ragged_k) {
 moe_status_t launch_gemm_mfma(const GemmP& p, int epi, bool ragged_k, hipStream_t s) {
   if (ragged_k) return launch_cfg<TR, TR, EPI_PLAIN, true>(p, s);
   const bool b_kc = p.sBk == 1;  // B(k,n) = W[n][k]: the dgrad products
+#ifdef MOE_DEBUG_SWITCHES
   static const bool force_k32 = getenv("MOE_GEMM_K32") != nullptr;  // for A/B timing of the two K pipelines
+#else
+  constexpr bool force_k32 = false;
+#endif
   if (p.Kfix % BK2 == 0 && !force_k32) {
     switch (epi) {
       case EPI_PLAIN:

@@ -16,6 +16,8 @@
 // routing that matches an independent oracle bit for bit whatever the summation order.
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "common.h"
 #include "gemm_params.h"
 
@@ -119,7 +121,8 @@ __device__ __forceinline__ void gate_tail(float* __restrict__ lg, int32_t* __res
       int tk = i / n_experts, e = i % n_experts;
       if (t0 + tk < n_tokens) logits[(size_t)(t0 + tk) * n_experts + e] = lg[tk * lgs + e];
     }
-    if (mode == kGateLogitsOnly) return;
+    if (mode == kGateLogitsOnly) return;  // the same for every thread of the block
+    __syncthreads();  // wave 0 overwrites lg with G(I) below: every wave has copied its logits out by then
   }
 
   // top-k and G(I): one token per lane of wave 0
@@ -572,21 +575,42 @@ __global__ __launch_bounds__(256) void positions_kernel(const int32_t* __restric
   for (int r = a + blockIdx.x * blockDim.x + threadIdx.x; r < all; r += gridDim.x * blockDim.x) src_of_row[r] = -1;
 }
 
+// Kernels that use more than 64 KB of LDS need the attribute below once per device.  A host-side call (no stream
+// work, so it is legal under stream capture); done on the first launch on each device, from whichever thread
+// gets there first (setting it twice is harmless, so a racing second thread just sets it again).
+template <typename K>
+moe_status_t allow_full_lds(K kernel, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    set_error("gate: no current device");
+    return MOE_ERR_DEVICE;
+  }
+  const uint64_t bit = 1ull << dev;
+  if (done.load(std::memory_order_acquire) & bit) return MOE_OK;
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           160 * 1024);
+  if (e != hipSuccess) {
+    set_error("gate: hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed: %s", hipGetErrorString(e));
+    return MOE_ERR_DEVICE;
+  }
+  done.fetch_or(bit, std::memory_order_release);
+  return MOE_OK;
+}
+
 template <typename T, int NEG>
-void launch_gate(const moe_config_t& c, const RoutePlan& p, const void* x, const double* wd, const float* b_gate,
+moe_status_t launch_gate(const moe_config_t& c, const RoutePlan& p, const void* x, const double* wd, const float* b_gate,
                  float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* hist, const float* noise,
                  const float* noise_logits, int mode, hipStream_t s) {
   constexpr int EE = 8 * NEG;
   const size_t lds = gate_lds_bytes(EE, c.n_experts, c.top_k);
-  static bool attr_set = false;  // LDS above 64 KB must be requested once per kernel
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gate_topk_kernel<T, NEG>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> attr_done{0};
+  const moe_status_t st = allow_full_lds(gate_topk_kernel<T, NEG>, attr_done);
+  if (st != MOE_OK) return st;
   hipLaunchKernelGGL((gate_topk_kernel<T, NEG>), dim3(p.nb), dim3(kGateThreads), lds, s, (const T*)x, wd, b_gate, logits,
                      probs, topk_idx, topk_w, hist, c.n_tokens, c.d_model, c.n_experts, c.top_k, c.renormalize, p.ep,
                      p.nkc, p.nb, noise, noise_logits, mode);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
 }
 
 template <typename T>
@@ -606,15 +630,16 @@ moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, c
   // the kernel that reads x straight into registers, whenever the W_g rows of 8 experts fit in LDS (M up to
   // about 8000 in bf16); measured faster than gate_topk_kernel at every shape tried (2x at E = 8, 1.1x at 32 and 64,
   // 1.4x at 256)
+#ifdef MOE_DEBUG_SWITCHES
   static const bool force_wide = getenv("MOE_GATE_WIDE") != nullptr;  // for A/B timing of the two gate kernels
+#else
+  constexpr bool force_wide = false;
+#endif
   const size_t small_lds = small_gate_lds_bytes(c.d_model, c.n_experts, c.top_k, SmallGate<T>::kV);
   if (mode != kGateFromLogits && small_lds <= (size_t)160 * 1024 && !force_wide) {
-    static bool attr_set = false;  // LDS above 64 KB must be requested once per kernel
-    if (!attr_set) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gate_small_kernel<T>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      attr_set = true;
-    }
+    static std::atomic<uint64_t> attr_done{0};
+    const moe_status_t ast = allow_full_lds(gate_small_kernel<T>, attr_done);
+    if (ast != MOE_OK) return ast;
     hipLaunchKernelGGL(gate_small_kernel<T>, dim3(p.nb), dim3(kSmallThreads), small_lds, s, (const T*)x, (const T*)w_gate,
                        b_gate, logits, probs, topk_idx, topk_w, hist, c.n_tokens, c.d_model, c.n_experts, c.top_k,
                        c.renormalize, p.nb, noise, noise_logits, mode);
@@ -625,13 +650,14 @@ moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, c
                        c.n_experts, p.mpad, p.ep);
     MOE_CHECK_LAUNCH();
   }
+  moe_status_t gst;
   switch (p.ee) {
-    case 8: launch_gate<T, 1>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
-    case 16: launch_gate<T, 2>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
-    case 32: launch_gate<T, 4>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
-    default: launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
+    case 8: gst = launch_gate<T, 1>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
+    case 16: gst = launch_gate<T, 2>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
+    case 32: gst = launch_gate<T, 4>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
+    default: gst = launch_gate<T, 8>(c, p, x, wd, b_gate, logits, probs, topk_idx, topk_w, hist, noise, noise_logits, mode, s); break;
   }
-  MOE_CHECK_LAUNCH();
+  if (gst != MOE_OK) return gst;
   }
   if (mode == kGateLogitsOnly) return MOE_OK;
   hipLaunchKernelGGL(scan_hist_kernel, dim3(c.n_experts), dim3(256), 0, s, hist, total, c.top_k * p.nb);
@@ -1364,6 +1390,7 @@ moe_status_t route_xmoe_bwd_t(const moe_config_t& c, const void* x, const void* 
 }  // namespace
 
 size_t route_workspace_bytes(const moe_config_t& c) { return route_plan(c).bytes; }
+
 size_t route_bwd_workspace_bytes(const moe_config_t& c) { return route_bwd_plan(c).bytes; }
 
 moe_status_t launch_route(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
