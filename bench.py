@@ -57,16 +57,30 @@ def parse():
     return ap.parse_args()
 
 
-def library_gemm_reference(torch, m=32768, n=4096, k=14336, secs=1.0):
-    """Sustained TFLOP/s of torch.matmul (hipBLASLt) in bf16 on one dense product of the size of the Mixtral
-    q = hh.W2 product with all experts merged; B row-major [k,n] ("NN") and B = W^T with W [n,k] ("NT")."""
-    a = torch.randn(m, k, device="cuda", dtype=torch.bfloat16)
+def library_gemm_reference(torch, m=32768, n=4096, k=14336, secs=0.7):
+    """Sustained TFLOP/s of torch.matmul (the vendor library) in bf16 on dense products of the size of the Mixtral
+    expert products with all experts merged, one per operand layout of the path:
+      NN: A [m,k] . B [k,n], B row-major             (forward: xe.W1, hh.W2)
+      NT: A [m,k] . W^T with W [n,k]                 (backward of the inputs: dq.W2^T, da.W1^T)
+      TN: A^T . B with A [m,k'], B [m,n], k' = k     (weight gradients: hh^T.dq, contraction over the m rows)"""
     out = {}
-    for name in ("NN", "NT"):
-        b = torch.randn((k, n) if name == "NN" else (n, k), device="cuda", dtype=torch.bfloat16) * 0.02
-        bb = b if name == "NN" else b.t()
-        c = torch.empty(m, n, device="cuda", dtype=torch.bfloat16)
-        torch.matmul(a, bb, out=c)
+    for name in ("NN", "NT", "TN"):
+        a = torch.randn(m, k, device="cuda", dtype=torch.bfloat16)
+        if name == "NN":
+            b = torch.randn(k, n, device="cuda", dtype=torch.bfloat16) * 0.02
+            c = torch.empty(m, n, device="cuda", dtype=torch.bfloat16)
+            fn = lambda: torch.matmul(a, b, out=c)
+        elif name == "NT":
+            b = torch.randn(n, k, device="cuda", dtype=torch.bfloat16) * 0.02
+            c = torch.empty(m, n, device="cuda", dtype=torch.bfloat16)
+            bt = b.t()
+            fn = lambda: torch.matmul(a, bt, out=c)
+        else:
+            b = torch.randn(m, n, device="cuda", dtype=torch.bfloat16)
+            c = torch.empty(k, n, device="cuda", dtype=torch.bfloat16)
+            at = a.t()
+            fn = lambda: torch.matmul(at, b, out=c)
+        fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         rates = []
@@ -74,14 +88,14 @@ def library_gemm_reference(torch, m=32768, n=4096, k=14336, secs=1.0):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(10):
-                torch.matmul(a, bb, out=c)
+                fn()
             e1.record()
             torch.cuda.synchronize()
             rates.append(2.0 * m * n * k * 10 / e0.elapsed_time(e1) / 1e9)
         half = rates[len(rates) // 2:]
         out[name] = round(sum(half) / len(half), 1)
-        del b, bb, c
-    return {"what": f"torch.matmul bf16 {m}x{n}x{k}, sustained, TFLOP/s", **out}
+        del a, b, c
+    return {"what": f"torch.matmul bf16, {m} x {n} x {k} (NN, NT) and {k} x {n} x {m} (TN), sustained, TFLOP/s", **out}
 
 
 def fit_expert_model(torch, cfg, w, d, b, xe, a1, a3, hh, count, timed, reps, fwd_flop):
@@ -148,8 +162,7 @@ def main():
     import torch
     import moe_synth as S
     import paper_2501_10714_amd as moe
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from moe_harness import Buffers, cap_of, make_cfg
+    from paper_2501_10714_amd.buffers import Buffers, make_cfg   # allocation only; the oracle is loaded by cpu_baseline() alone
 
     moe.load()                                           # fails loudly when the HIP library is missing
     torch.cuda.set_device(0)
@@ -304,7 +317,7 @@ def main():
 
 def time_gates(torch, moe, S, w, d, args, ms_default):
     """ms per layer step (forward + backward) with each gate of Sec. 2.1, same N, M, H, E and expert weights."""
-    from moe_harness import Buffers, make_cfg
+    from paper_2501_10714_amd.buffers import Buffers, make_cfg
     dt = d["x"].dtype
     i32, f32 = torch.int32, torch.float32
     names = [("logits", f32), ("probs", f32), ("topk_idx", i32), ("topk_w", f32), ("pos", i32), ("row_of", i32),

@@ -8,12 +8,9 @@ import torch
 import moe_synth as S
 import paper_2501_10714_amd as moe
 from oracle import moe_oracle as O
+from paper_2501_10714_amd.buffers import Buffers, capacity_of, make_cfg, tdtype  # noqa: F401  (no oracle in there)
 
 TOL = {S.DT_BF16: 2e-2, S.DT_F32: 1e-5}   # max |gpu - oracle| / max |oracle| per tensor
-
-
-def tdtype(w):
-    return torch.bfloat16 if w.dtype == S.DT_BF16 else torch.float32
 
 
 def to_dev(a, dev="cuda"):
@@ -49,13 +46,44 @@ def rel_err(got, want):
     return float(np.max(np.abs(got - want))) / max(scale, 1e-30)
 
 
+def violations(got, want, tol):
+    """Number of elements with |got - want| > tol * |want| + tol * rms(want): the element-wise companion of
+    rel_err, which guards the small entries of a tensor that the max-norm measure does not see."""
+    want = np.asarray(want, np.float64)
+    got = np.asarray(got, np.float64)
+    if want.size == 0:
+        return 0
+    rms = float(np.sqrt(np.mean(want * want)))
+    return int(np.count_nonzero(np.abs(got - want) > tol * np.abs(want) + tol * rms))
+
+
+# Share of the elements of a tensor that may miss the element-wise bound.  The bound is 2 % of the element plus 2 %
+# of the tensor's rms.  A bf16 result carries one rounding (2^-9 of its own size) plus the roundings of the bf16
+# intermediates it was formed from (a1, a3, hh, dq, da1, da3); measured, the rms of the error is 0.3 - 0.4 % of the
+# tensor's rms.  For sums over thousands of rows the error is Gaussian and 2 % is never reached; a weight gradient
+# of an expert with a few dozen rows is dominated by single rows whose error is a product of three rounded factors
+# (heavy-tailed), and a few elements in 10^4 reach 2 - 2.5 % of the rms (seen: 5 of 32768 for an expert of 23 rows).
+# A mis-addressed row or column tile, the mistake this measure is for, puts 10 % or more of a sampled tensor outside
+# the bound, so the bar sits two orders of magnitude below that and one above what rounding produces.
+VIOLATION_SHARE = 1e-3
+
+
+def check(got, want, tol, name=""):
+    """Both measures of parity on one tensor: max |gpu - oracle| / max |oracle| <= tol, and at most
+    VIOLATION_SHARE of the elements outside |d| <= tol |oracle| + tol rms(oracle)."""
+    r = rel_err(got, want)
+    assert r <= tol, f"{name}: max relative error {r:.3e} > {tol:.1e}"
+    n = violations(got, want, tol)
+    size = int(np.asarray(want).size)
+    assert n <= int(VIOLATION_SHARE * size), f"{name}: {n} of {size} elements outside rtol = atol/rms = {tol:.1e}"
+    return r, n
+
+
 def cap_of(w):
-    return 0 if w.f is None else O.capacity(w.N, w.E, w.k, w.f)
-
-
-def make_cfg(w, capacity=None, accumulate=0):
-    cap = cap_of(w) if capacity is None else capacity
-    return moe.MoeConfig.make(w.N, w.M, w.E, w.H, w.k, cap, w.dtype, w.act, w.renormalize, w.add_residual, accumulate)
+    """Capacity of a workload: the product's moe_capacity, which must agree with the oracle's formula."""
+    cap = capacity_of(w)
+    assert cap == (0 if w.f is None else O.capacity(w.N, w.E, w.k, w.f)), "moe_capacity differs from the oracle"
+    return cap
 
 
 def f64_inputs(d):
@@ -71,35 +99,6 @@ def oracle_layer(w, d, capacity=None):
     bwd = O.layer_bwd(f["dy"], f["x"], f["w_gate"], f["b_gate"], f["w1"], f["w3"], f["w2"], fwd, w.act, w.renormalize,
                       w.add_residual)
     return f, fwd, bwd
-
-
-class Buffers:
-    """Device buffers for every output of the path, sized as the header says (N*k expert rows)."""
-
-    def __init__(self, w, cfg, dev="cuda"):
-        N, M, E, H, k = w.N, w.M, w.E, w.H, w.k
-        A = N * k
-        dt = tdtype(w)
-        i32 = dict(dtype=torch.int32, device=dev)
-        f32 = dict(dtype=torch.float32, device=dev)
-        el = dict(dtype=dt, device=dev)
-        ws_bytes, saved_bytes = moe.moe_workspace_bytes(cfg)
-        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-        self.saved = torch.empty(saved_bytes, dtype=torch.uint8, device=dev)
-        self.logits = torch.empty(N, E, **f32); self.probs = torch.empty(N, E, **f32)
-        self.topk_idx = torch.empty(N, k, **i32); self.topk_w = torch.empty(N, k, **f32)
-        self.pos = torch.empty(N, k, **i32); self.row_of = torch.empty(N, k, **i32)
-        self.count = torch.empty(E, **i32); self.offsets = torch.empty(E + 1, **i32)
-        self.src_of_row = torch.empty(A, **i32)
-        self.xe = torch.empty(A, M, **el); self.q = torch.empty(A, M, **el)
-        self.a1 = torch.empty(A, H, **el); self.hh = torch.empty(A, H, **el)
-        self.a3 = torch.empty(A, H, **el) if w.gated else None
-        self.y = torch.empty(N, M, **el); self.dx = torch.empty(N, M, **el)
-        self.dq = torch.empty(A, M, **el); self.dxe = torch.empty(A, M, **el)
-        self.dtopk_w = torch.empty(N, k, **f32)
-        self.dw_gate = torch.empty(M, E, **el); self.db_gate = torch.empty(E, **f32)
-        self.dw1 = torch.empty(E, M, H, **el); self.dw2 = torch.empty(E, H, M, **el)
-        self.dw3 = torch.empty(E, M, H, **el) if w.gated else None
 
 
 def dev_inputs(d):

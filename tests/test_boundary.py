@@ -41,6 +41,17 @@ def test_capacity_matches_formula(lib):
     assert moe.moe_capacity(0, 4, 1, 1.0) == -1 and moe.moe_capacity(8, 4, 1, -1.0) == -1
 
 
+def test_capacity_equals_the_oracle_over_a_sweep(lib):
+    """moe_capacity (the product) against the oracle's T = ceil(k f N / E), on values where the product k f N / E is
+    a whole number, just above one, or not representable."""
+    from oracle import moe_oracle as O
+    for n in (1, 7, 256, 1000, 8192, 32768, 65536, 99999):
+        for e in (1, 3, 4, 16, 32, 64, 130, 256):
+            for k in (1, 2, 6, 8):
+                for f in (0.25, 0.3, 1.0, 1.1, 1.2, 1.25, 1.5, 2.0, 7.3):
+                    assert moe.moe_capacity(n, e, k, f) == O.capacity(n, e, k, f), (n, e, k, f)
+
+
 def test_config_validation(lib):
     ok = moe.MoeConfig.make(64, 64, 4, 128, 2, 0, moe.DT_F32, moe.ACT_RELU)
     ws, sv = moe.moe_workspace_bytes(ok)
@@ -115,3 +126,22 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "one-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_the_product_path_never_reaches_the_oracle():
+    """Nothing under the package imports oracle/ or tests/, and bench.py does so only inside its cpu_baseline leg."""
+    import ast
+    pkg = os.path.join(ROOT, "paper_2501_10714_amd")
+    for fn in sorted(os.listdir(pkg)):
+        if fn.endswith(".py"):
+            text = open(os.path.join(pkg, fn)).read()
+            assert "oracle" not in text and "moe_harness" not in text, fn
+    tree = ast.parse(open(os.path.join(ROOT, "bench.py")).read())
+    for node in ast.walk(tree):
+        if isinstance(node, ast.FunctionDef):
+            uses = [n for n in ast.walk(node) if isinstance(n, (ast.Import, ast.ImportFrom))
+                    and "oracle" in (getattr(n, "module", None) or " ".join(a.name for a in n.names))]
+            assert not uses or node.name == "cpu_baseline", node.name
+    top = [n for n in tree.body if isinstance(n, (ast.Import, ast.ImportFrom))]
+    assert all("oracle" not in (getattr(n, "module", None) or " ".join(a.name for a in n.names)) for n in top)
+    assert "moe_harness" not in open(os.path.join(ROOT, "bench.py")).read()

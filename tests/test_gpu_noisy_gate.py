@@ -6,7 +6,7 @@ import torch
 
 import moe_synth as S
 import paper_2501_10714_amd as moe
-from moe_harness import TOL, Buffers, assert_routing_equal, cap_of, make_cfg, rel_err, store, to_dev, to_np
+from moe_harness import check, TOL, Buffers, assert_routing_equal, cap_of, make_cfg, rel_err, store, to_dev, to_np
 from oracle import moe_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -37,8 +37,8 @@ def test_noisy_route_forward_and_backward(name):
     got_logits = b.logits.cpu().numpy()
     assert np.array_equal(got_logits, ref["logits"]), f"{np.count_nonzero(got_logits != ref['logits'])} logits differ in bits"
     assert_routing_equal({n: to_np(getattr(b, n)) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}, ref)
-    assert rel_err(to_np(b.probs), ref["probs"]) <= 1e-5
-    assert rel_err(to_np(b.topk_w), ref["topk_w"]) <= 1e-5
+    check(to_np(b.probs), ref["probs"], 1e-5)
+    check(to_np(b.topk_w), ref["topk_w"], 1e-5)
     # the noise changes decisions: the same inputs without it route differently somewhere
     plain = O.route(f(x), f(wg), None if bg is None else f(bg), w.k, cap, w.renormalize)
     assert (plain["topk_idx"] != ref["topk_idx"]).any()
@@ -55,8 +55,8 @@ def test_noisy_route_forward_and_backward(name):
                             b.dw_gate, b.db_gate if bg is not None else None, dw_noise, b.dx, b.ws)
     torch.cuda.synchronize()
     tol = TOL[w.dtype]
-    assert rel_err(to_np(b.dw_gate), dwg) <= tol
-    assert rel_err(to_np(dw_noise), dwn) <= tol
-    assert rel_err(to_np(b.dx), S.to_f64(base) + dx) <= tol
+    check(to_np(b.dw_gate), dwg, tol)
+    check(to_np(dw_noise), dwn, tol)
+    check(to_np(b.dx), S.to_f64(base) + dx, tol)
     if bg is not None:
-        assert rel_err(to_np(b.db_gate), dbg) <= 1e-4
+        check(to_np(b.db_gate), dbg, 1e-4)

@@ -12,7 +12,7 @@ import torch
 import moe_synth as S
 import paper_2501_10714_amd as moe
 from oracle import moe_oracle as O
-from moe_harness import (TOL, Buffers, assert_routing_equal, cap_of, dev_inputs, f64_inputs, make_cfg, oracle_layer,
+from moe_harness import (check, TOL, Buffers, assert_routing_equal, cap_of, dev_inputs, f64_inputs, make_cfg, oracle_layer,
                          rel_err, run_layer, saved_np, store, to_dev, to_np)
 
 pytestmark = pytest.mark.gpu
@@ -81,8 +81,8 @@ def test_route(name, solved):
     logits = b.logits.cpu().numpy()
     assert np.array_equal(logits, fwd["logits"]), f"{np.count_nonzero(logits != fwd['logits'])} logits differ in bits"
     assert_routing_equal(routing_dict(b), fwd)
-    assert rel_err(to_np(b.probs), fwd["probs"]) <= 1e-5
-    assert rel_err(to_np(b.topk_w), fwd["topk_w"]) <= 1e-5
+    check(to_np(b.probs), fwd["probs"], 1e-5)
+    check(to_np(b.topk_w), fwd["topk_w"], 1e-5)
     if w.f is not None:
         assert int(b.count.max()) <= cap_of(w)
 
@@ -105,22 +105,22 @@ def test_dispatch_and_combine(name, solved):
     moe.moe_combine(cfg, q_dev, topk_w, row_of, dd["x"], b.y)
     want = O.inverse_order(S.to_f64(q_st), fwd["topk_w"].astype(np.float32).astype(np.float64), fwd["row_of"],
                            f["x"] if w.add_residual else None)
-    assert rel_err(to_np(b.y), want) <= TOL[w.dtype] * (0.25 if w.dtype == S.DT_BF16 else 1)
+    check(to_np(b.y), want, TOL[w.dtype] * (0.25 if w.dtype == S.DT_BF16 else 1))
     dropped_all = np.all(fwd["pos"] < 0, axis=1)
     if dropped_all.any() and not w.add_residual:
         assert np.all(to_np(b.y)[dropped_all] == 0)
     # combine backward
     moe.moe_combine_bwd(cfg, dd["dy"], q_dev, topk_w, row_of, b.dq, b.dtopk_w)
     dq, dtw = O.inverse_order_bwd(f["dy"], S.to_f64(q_st), fwd["topk_w"].astype(np.float32).astype(np.float64), fwd["row_of"])
-    assert rel_err(to_np(b.dq[:A]), dq) <= TOL[w.dtype] * (0.25 if w.dtype == S.DT_BF16 else 1)
-    assert rel_err(to_np(b.dtopk_w), dtw) <= 1e-5
+    check(to_np(b.dq[:A]), dq, TOL[w.dtype] * (0.25 if w.dtype == S.DT_BF16 else 1))
+    check(to_np(b.dtopk_w), dtw, 1e-5)
     assert np.all(to_np(b.dtopk_w)[fwd["pos"] < 0] == 0)
     # dispatch backward on the oracle's dxe
     dxe_st = store(bwd["dxe"], w)
     dxe_dev = torch.zeros_like(b.dxe); dxe_dev[:A] = to_dev(dxe_st)
     moe.moe_dispatch_bwd(cfg, dxe_dev, row_of, dd["dy"] if w.add_residual else None, b.dx)
     want = O.order_bwd(S.to_f64(dxe_st), fwd["row_of"], f["dy"] if w.add_residual else None)
-    assert rel_err(to_np(b.dx), want) <= TOL[w.dtype] * (0.25 if w.dtype == S.DT_BF16 else 1)
+    check(to_np(b.dx), want, TOL[w.dtype] * (0.25 if w.dtype == S.DT_BF16 else 1))
 
 
 @pytest.mark.parametrize("name", list(CASES))
@@ -136,11 +136,11 @@ def test_expert_ffn(name, solved):
     moe.moe_expert_ffn_fwd(cfg, xe_dev, offsets, dd["w1"], dd["w3"], dd["w2"], b.q, b.a1, b.a3, b.hh, b.ws)
     torch.cuda.synchronize()
     a1, a3, hh = fwd["saved"]
-    assert rel_err(to_np(b.a1[:A]), a1) <= tol
-    assert rel_err(to_np(b.hh[:A]), hh) <= tol
+    check(to_np(b.a1[:A]), a1, tol)
+    check(to_np(b.hh[:A]), hh, tol)
     if w.gated:
-        assert rel_err(to_np(b.a3[:A]), a3) <= tol
-    assert rel_err(to_np(b.q[:A]), fwd["q"]) <= tol
+        check(to_np(b.a3[:A]), a3, tol)
+    check(to_np(b.q[:A]), fwd["q"], tol)
     # backward from the oracle's stored activations and dq (rounded to storage)
     st = {n: store(v, w) for n, v in (("dq", bwd["dq"]), ("a1", a1), ("hh", hh))}
     if w.gated:
@@ -154,11 +154,11 @@ def test_expert_ffn(name, solved):
     s64 = {n: S.to_f64(v) for n, v in st.items()}
     dxe, dw1, dw3, dw2 = O.expert_ffn_bwd(s64["dq"], fwd["xe"], fwd["offsets"], f["w1"], f["w3"], f["w2"],
                                           (s64["a1"], s64.get("a3"), s64["hh"]), w.act)
-    assert rel_err(to_np(b.dxe[:A]), dxe) <= tol
-    assert rel_err(to_np(b.dw1), dw1) <= tol
-    assert rel_err(to_np(b.dw2), dw2) <= tol
+    check(to_np(b.dxe[:A]), dxe, tol)
+    check(to_np(b.dw1), dw1, tol)
+    check(to_np(b.dw2), dw2, tol)
     if w.gated:
-        assert rel_err(to_np(b.dw3), dw3) <= tol
+        check(to_np(b.dw3), dw3, tol)
 
 
 @pytest.mark.parametrize("name", list(CASES))
@@ -188,10 +188,10 @@ def test_route_bwd(name, solved):
     else:
         dl = p * (g - (g * p).sum(1, keepdims=True))
     tol = TOL[w.dtype]
-    assert rel_err(to_np(b.dw_gate), f["x"].T @ dl) <= tol
-    assert rel_err(to_np(b.dx), S.to_f64(base) + dl @ f["w_gate"].T) <= tol
+    check(to_np(b.dw_gate), f["x"].T @ dl, tol)
+    check(to_np(b.dx), S.to_f64(base) + dl @ f["w_gate"].T, tol)
     if d["b_gate"] is not None:
-        assert rel_err(to_np(b.db_gate), dl.sum(0)) <= 1e-5 * 10
+        check(to_np(b.db_gate), dl.sum(0), 1e-5 * 10)
 
 
 @pytest.mark.parametrize("name", list(CASES))
@@ -203,15 +203,15 @@ def test_layer_fwd_bwd(name, solved):
     got = {n: v.reshape(np.asarray(fwd[n]).shape) for n, v in got.items()}
     assert_routing_equal(got, fwd)
     assert np.array_equal(saved_np(cfg, b, "logits", torch.float32).reshape(w.N, w.E), fwd["logits"].astype(np.float64))
-    assert rel_err(to_np(b.y), fwd["y"]) <= tol
-    assert rel_err(to_np(b.dx), bwd["dx"]) <= tol
-    assert rel_err(to_np(b.dw_gate), bwd["dw_gate"]) <= tol
-    assert rel_err(to_np(b.dw1), bwd["dw1"]) <= tol
-    assert rel_err(to_np(b.dw2), bwd["dw2"]) <= tol
+    check(to_np(b.y), fwd["y"], tol)
+    check(to_np(b.dx), bwd["dx"], tol)
+    check(to_np(b.dw_gate), bwd["dw_gate"], tol)
+    check(to_np(b.dw1), bwd["dw1"], tol)
+    check(to_np(b.dw2), bwd["dw2"], tol)
     if w.gated:
-        assert rel_err(to_np(b.dw3), bwd["dw3"]) <= tol
+        check(to_np(b.dw3), bwd["dw3"], tol)
     if d["b_gate"] is not None:
-        assert rel_err(to_np(b.db_gate), bwd["db_gate"]) <= tol
+        check(to_np(b.db_gate), bwd["db_gate"], tol)
     # run to run: bit identical
     y1, dx1, dw1 = b.y.clone(), b.dx.clone(), b.dw1.clone()
     cfg, b = run_layer(w, d, bufs=b)
@@ -224,7 +224,7 @@ def test_plain_and_mfma_gemm_agree_with_oracle(solved, monkeypatch):
     monkeypatch.setenv("MOE_FORCE_PLAIN_GEMM", "1")
     cfg, b = run_layer(w, d)
     for name, want in (("y", fwd["y"]), ("dx", bwd["dx"]), ("dw1", bwd["dw1"]), ("dw2", bwd["dw2"]), ("dw3", bwd["dw3"])):
-        assert rel_err(to_np(getattr(b, name)), want) <= TOL[w.dtype], name
+        check(to_np(getattr(b, name)), want, TOL[w.dtype], str(name))
 
 
 # ----------------------------------------------------------------------------- edge cases
@@ -240,12 +240,12 @@ def test_expert_without_tokens_and_accumulate():
     assert_routing_equal(got, fwd)
     dw1 = to_np(b.dw1)
     assert np.all(dw1[fwd["count"] == 0] == 0)
-    assert rel_err(dw1, bwd["dw1"]) <= TOL[w.dtype]
+    check(dw1, bwd["dw1"], TOL[w.dtype])
     # accumulate_wgrad: a second backward adds the same gradient again
     first = {n: getattr(b, n).float().clone() for n in ("dw1", "dw2")}
     cfg2, b = run_layer(w, d, accumulate=1, bufs=b)
     for n in ("dw1", "dw2"):
-        assert rel_err(to_np(getattr(b, n)), 2 * first[n].cpu().numpy().astype(np.float64)) <= TOL[w.dtype]
+        check(to_np(getattr(b, n)), 2 * first[n].cpu().numpy().astype(np.float64), TOL[w.dtype])
 
 
 def test_capacity_one_drops_almost_everything():
@@ -256,8 +256,8 @@ def test_capacity_one_drops_almost_everything():
     cfg, b = run_layer(w, d, capacity=1)
     got = {n: saved_np(cfg, b, n, torch.int32).reshape(np.asarray(fwd[n]).shape) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}
     assert_routing_equal(got, fwd)
-    assert rel_err(to_np(b.y), fwd["y"]) <= TOL[w.dtype]
-    assert rel_err(to_np(b.dx), bwd["dx"]) <= TOL[w.dtype]
+    check(to_np(b.y), fwd["y"], TOL[w.dtype])
+    check(to_np(b.dx), bwd["dx"], TOL[w.dtype])
     dropped = np.all(fwd["pos"] < 0, axis=1)
     assert np.array_equal(to_np(b.y)[dropped], f["x"][dropped])      # residual passthrough, exact
 
@@ -272,7 +272,7 @@ def test_all_experts_selected_identical_experts_is_dense_ffn():
     x = d["x"].astype(np.float64)
     a1, a3 = x @ d["w1"][0].astype(np.float64), x @ d["w3"][0].astype(np.float64)
     dense = (a1 / (1 + np.exp(-a1)) * a3) @ d["w2"][0].astype(np.float64)
-    assert rel_err(to_np(b.y), dense) <= 1e-5
+    check(to_np(b.y), dense, 1e-5)
 
 
 def test_exact_ties_go_to_the_lower_expert():
@@ -313,7 +313,7 @@ def test_expert_choice_ties_and_signed_zeros():
                       b.count, b.offsets, b.src_of_row, b.ws)
         torch.cuda.synchronize()
         assert_routing_equal(routing_dict(b), ref)
-        assert rel_err(to_np(b.topk_w), ref["topk_w"]) <= 1e-5
+        check(to_np(b.topk_w), ref["topk_w"], 1e-5)
 
 
 def test_nan_logits_still_give_valid_routing():

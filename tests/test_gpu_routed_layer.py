@@ -9,7 +9,7 @@ import torch
 
 import moe_synth as S
 import paper_2501_10714_amd as moe
-from moe_harness import TOL, Buffers, cap_of, dev_inputs, make_cfg, rel_err, run_layer, to_dev, to_np
+from moe_harness import check, TOL, Buffers, cap_of, dev_inputs, make_cfg, rel_err, run_layer, to_dev, to_np
 from oracle import moe_oracle as O
 from test_gpu_parity import CASES
 from test_gpu_xmoe_gate import CASES as XCASES
@@ -99,15 +99,15 @@ def test_xmoe_layer_through_the_routed_calls(name, r):
     torch.cuda.synchronize()
     assert np.array_equal(to_np(v["row_of"]).reshape(w.N, w.k), ro["row_of"])
     tol = TOL[w.dtype]
-    assert rel_err(to_np(b.y), y) <= tol
-    assert rel_err(to_np(b.dtopk_w), dtw) <= tol
-    assert rel_err(to_np(b.dx), dx + dx_gate) <= tol
-    assert rel_err(to_np(dw_proj), dwp) <= tol
-    assert rel_err(to_np(dw_gate), dwg) <= tol
-    assert rel_err(to_np(b.dw1), dw1) <= tol
-    assert rel_err(to_np(b.dw2), dw2) <= tol
+    check(to_np(b.y), y, tol)
+    check(to_np(b.dtopk_w), dtw, tol)
+    check(to_np(b.dx), dx + dx_gate, tol)
+    check(to_np(dw_proj), dwp, tol)
+    check(to_np(dw_gate), dwg, tol)
+    check(to_np(b.dw1), dw1, tol)
+    check(to_np(b.dw2), dw2, tol)
     if w.gated:
-        assert rel_err(to_np(b.dw3), dw3) <= tol
+        check(to_np(b.dw3), dw3, tol)
 
 
 def test_routed_calls_check_their_arguments():

@@ -6,7 +6,7 @@ import torch
 
 import moe_synth as S
 import paper_2501_10714_amd as moe
-from moe_harness import TOL, Buffers, assert_routing_equal, cap_of, make_cfg, rel_err, store, to_dev, to_np
+from moe_harness import check, TOL, Buffers, assert_routing_equal, cap_of, make_cfg, rel_err, store, to_dev, to_np
 from oracle import moe_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -43,8 +43,8 @@ def test_xmoe_route_forward_and_backward(name):
     assert np.array_equal(got, ref["logits"]), f"{np.count_nonzero(got != ref['logits'])} scores differ in bits"
     assert np.abs(got).max() <= 1.0
     assert_routing_equal({n: to_np(getattr(b, n)) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}, ref)
-    assert rel_err(to_np(b.probs), ref["probs"]) <= 1e-5
-    assert rel_err(to_np(b.topk_w), ref["topk_w"]) <= 1e-5
+    check(to_np(b.probs), ref["probs"], 1e-5)
+    check(to_np(b.topk_w), ref["topk_w"], 1e-5)
 
     # backward from the oracle's forward tensors (rounded to what the call takes)
     ds, dwp, dwg, dx = O.gate_bwd_xmoe(f(x), f(wp), f(wg), ref["proj"], ref["logits"], ref["topk_idx"], ref["pos"],
@@ -58,9 +58,9 @@ def test_xmoe_route_forward_and_backward(name):
                            dw_proj, dw_gate, b.dx, ws)
     torch.cuda.synchronize()
     tol = TOL[w.dtype]
-    assert rel_err(to_np(dw_proj), dwp) <= tol
-    assert rel_err(to_np(dw_gate), dwg) <= tol
-    assert rel_err(to_np(b.dx), S.to_f64(base) + dx) <= tol
+    check(to_np(dw_proj), dwp, tol)
+    check(to_np(dw_gate), dwg, tol)
+    check(to_np(b.dx), S.to_f64(base) + dx, tol)
     # a second call on a smaller problem with the same workspace: nothing of the first may leak
     if name == "xmoe_bf16_topk":
         w2 = S.scaled(w, N=200)
@@ -132,11 +132,11 @@ def test_xmoe_layer_through_the_stage_calls(name):
     torch.cuda.synchronize()
     assert_routing_equal({n: to_np(getattr(b, n)) for n in ("topk_idx", "pos", "count", "offsets", "row_of", "src_of_row")}, r)
     tol = TOL[w.dtype]
-    assert rel_err(to_np(b.y), y) <= tol
-    assert rel_err(to_np(b.dx), dx + dx_gate) <= tol
-    assert rel_err(to_np(dw_proj), dwp) <= tol
-    assert rel_err(to_np(dw_gate), dwg) <= tol
-    assert rel_err(to_np(b.dw1), dw1) <= tol
-    assert rel_err(to_np(b.dw2), dw2) <= tol
+    check(to_np(b.y), y, tol)
+    check(to_np(b.dx), dx + dx_gate, tol)
+    check(to_np(dw_proj), dwp, tol)
+    check(to_np(dw_gate), dwg, tol)
+    check(to_np(b.dw1), dw1, tol)
+    check(to_np(b.dw2), dw2, tol)
     if w.gated:
-        assert rel_err(to_np(b.dw3), dw3) <= tol
+        check(to_np(b.dw3), dw3, tol)
