@@ -116,6 +116,23 @@ moe_status_t moe_route(const moe_config_t* cfg, const void* x, const void* w_gat
                        int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* moe_route for callers that cannot allocate device memory or carry a workspace around: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs, gates and errors as
+ * moe_route, without the workspace: the scratch of the gate kernels lives in a device array of
+ * MOE_ROUTE_STATIC_SCRATCH_BYTES that is part of the library (every GPU the library runs on holds it until the
+ * process ends).  The call allocates and frees nothing; its first use on a device looks up the array's address
+ * (hipGetSymbolAddress, host side) and, like moe_route, sets one kernel attribute.
+ * Limit: 256-byte-rounded  8 * ceil(M/64)*64 * Ep  (Ep = E rounded up to 8, 16, 32 or a multiple of 64)
+ *        + 4 * E * k * ceil(N/64)  + 4 * E  bytes must fit; all five benchmark shapes do (the largest, N = 32768,
+ *        M = 2048, E = 64, k = 6, needs 1.8 MB).  Larger shapes: MOE_ERR_WORKSPACE, nothing launched.
+ * All calls on one GPU share the one array, which keeps the last call's contents (nothing in it has to be
+ * cleared between calls): two moe_route_static calls that overlap on one GPU (different streams, no ordering
+ * between them) race and give undefined results; calls ordered on one stream are safe. */
+#define MOE_ROUTE_STATIC_SCRATCH_BYTES (4u << 20)
+moe_status_t moe_route_static(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
+                              float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos,
+                              int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row, void* stream);
+
 /* Ordering function (Sec. 2.1): xe[row_of[t,j], :] = x[t, :] for every kept assignment.  The
  * compact expert-major buffer xe [A,M] is the paper's (E,T,M) layout without its padding rows:
  * expert e owns rows offsets[e] .. offsets[e+1]-1.  Pure copy, bit exact. */

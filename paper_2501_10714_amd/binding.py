@@ -22,7 +22,7 @@ ENTRY_POINTS = ["moe_capacity", "moe_workspace_bytes", "moe_route", "moe_dispatc
                 "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_combine", "moe_combine_bwd", "moe_route_bwd",
                 "moe_layer_fwd", "moe_layer_bwd", "moe_layer_fwd_chunked", "moe_layer_bwd_chunked", "moe_saved_offset",
                 "moe_pipeline_time", "moe_find_pipeline_degree", "moe_route_noisy", "moe_route_noisy_bwd", "moe_route_xmoe_workspace_bytes",
-                "moe_route_xmoe", "moe_route_xmoe_bwd", "moe_layer_fwd_routed", "moe_layer_bwd_routed", "moe_last_error"]
+                "moe_route_xmoe", "moe_route_xmoe_bwd", "moe_layer_fwd_routed", "moe_layer_bwd_routed", "moe_route_static", "moe_last_error"]
 MAX_CHUNKS = 16  # MOE_MAX_CHUNKS
 
 
@@ -114,6 +114,12 @@ def moe_route(cfg, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_
     _check(load().moe_route(C.byref(cfg), _p(x), _p(w_gate), _p(b_gate), _p(logits), _p(probs), _p(topk_idx),
                             _p(topk_w), _p(pos), _p(row_of), _p(count), _p(offsets), _p(src_of_row), _p(ws), _sz(ws),
                             _stream()))
+
+
+def moe_route_static(cfg, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count, offsets, src_of_row):
+    """moe_route on the library's built-in scratch array: no workspace argument, nothing allocated."""
+    _check(load().moe_route_static(C.byref(cfg), _p(x), _p(w_gate), _p(b_gate), _p(logits), _p(probs), _p(topk_idx),
+                                   _p(topk_w), _p(pos), _p(row_of), _p(count), _p(offsets), _p(src_of_row), _stream()))
 
 
 def moe_dispatch(cfg, x, row_of, xe):

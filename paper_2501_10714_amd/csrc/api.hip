@@ -173,6 +173,16 @@ moe_status_t moe_route(const moe_config_t* cfg, const void* x, const void* w_gat
                       workspace, as_stream(stream));
 }
 
+moe_status_t moe_route_static(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
+                              float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos,
+                              int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row, void* stream) {
+  CHECK_CFG(cfg);
+  NOT_NULL(x); NOT_NULL(w_gate); NOT_NULL(logits); NOT_NULL(probs); NOT_NULL(topk_idx); NOT_NULL(topk_w);
+  NOT_NULL(pos); NOT_NULL(row_of); NOT_NULL(count); NOT_NULL(offsets); NOT_NULL(src_of_row);
+  return launch_route_static(*cfg, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count, offsets,
+                             src_of_row, as_stream(stream));
+}
+
 moe_status_t moe_route_noisy(const moe_config_t* cfg, const void* x, const void* w_gate, const float* b_gate,
                              const void* w_noise, const float* noise, float* logits, float* noise_logits, float* probs,
                              int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,

@@ -125,6 +125,9 @@ size_t route_workspace_bytes(const moe_config_t& c);
 moe_status_t launch_route(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
                           float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,
                           int32_t* offsets, int32_t* src_of_row, void* ws, hipStream_t s);
+moe_status_t launch_route_static(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate,
+                                 float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos,
+                                 int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row, hipStream_t s);
 moe_status_t launch_route_noisy(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate,
                                 const void* w_noise, const float* noise, float* logits, float* noise_logits, float* probs,
                                 int32_t* topk_idx, float* topk_w, int32_t* pos, int32_t* row_of, int32_t* count,

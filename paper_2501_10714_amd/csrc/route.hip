@@ -17,6 +17,7 @@
 #include <stdlib.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "common.h"
 #include "gemm_params.h"
@@ -1391,6 +1392,52 @@ moe_status_t route_xmoe_bwd_t(const moe_config_t& c, const void* x, const void* 
 
 size_t route_workspace_bytes(const moe_config_t& c) { return route_plan(c).bytes; }
 
+// ----------------------------------------------------------------------------- moe_route_static
+// The gate for callers that cannot allocate (code under stream capture, serving loops): the scratch that
+// moe_route takes as a workspace (the fp64 copy of W_g of the wide gate kernel, the histogram of choices per
+// (expert, rank, 64-token tile), the per-expert totals) lives in a device array of the library instead.  Every
+// GPU holds its own copy at its own address, looked up once per device; host code uses that address and never
+// the array's name.  Nothing in it has to start at zero: each kernel writes the parts the next one reads.
+namespace {
+static __device__ __align__(256) unsigned char scratch[MOE_ROUTE_STATIC_SCRATCH_BYTES];
+
+moe_status_t static_scratch_address(void** out) {
+  static std::mutex mu;
+  static void* per_device[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    set_error("moe_route_static: no current device");
+    return MOE_ERR_DEVICE;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (per_device[dev] == nullptr) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr) {
+      set_error("moe_route_static: hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+      return MOE_ERR_DEVICE;
+    }
+    per_device[dev] = ptr;
+  }
+  *out = per_device[dev];
+  return MOE_OK;
+}
+}  // namespace
+
+moe_status_t launch_route_static(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate,
+                                 float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* pos,
+                                 int32_t* row_of, int32_t* count, int32_t* offsets, int32_t* src_of_row, hipStream_t s) {
+  const size_t need = route_plan(c).bytes;
+  if (need > (size_t)MOE_ROUTE_STATIC_SCRATCH_BYTES) {
+    set_error("moe_route_static: this shape needs %zu bytes of scratch, the built-in buffer holds %zu (use moe_route)", need,
+              (size_t)MOE_ROUTE_STATIC_SCRATCH_BYTES);
+    return MOE_ERR_WORKSPACE;
+  }
+  void* ws = nullptr;
+  const moe_status_t st = static_scratch_address(&ws);
+  if (st != MOE_OK) return st;
+  return launch_route(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, pos, row_of, count, offsets, src_of_row, ws, s);
+}
 size_t route_bwd_workspace_bytes(const moe_config_t& c) { return route_bwd_plan(c).bytes; }
 
 moe_status_t launch_route(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate, float* logits,
