@@ -198,7 +198,7 @@ __device__ __forceinline__ int count_tiles(const GemmP& p, int n_nt, int mt_fix)
   for (int e = 0; e < p.n_experts; ++e) total += ((p.row_end[e] - p.offsets[e] + BM - 1) / BM) * n_nt;
   return total;
 }
-// Logical tile index L < count_tiles() -> (expert, row tile, column tile): per expert, bands of kBand
+// Logical tile index L < count_tiles() -> (expert, row tile, column tile): per expert, bands of about kBand
 // row tiles x all column tiles, row tile fastest inside a band.
 template <bool RAGGED_K>
 __device__ __forceinline__ TileId tile_at(const GemmP& p, int n_nt, int mt_fix, int L) {
@@ -215,11 +215,24 @@ __device__ __forceinline__ TileId tile_at(const GemmP& p, int n_nt, int mt_fix, 
       L -= cnt;
     }
   }
-  const int band = L / (kBand * n_nt);
-  const int rem = L - band * kBand * n_nt;
-  const int bsz = min(kBand, mt_g - band * kBand);
+  // The mt_g row tiles are cut into bands of nearly equal height, about kBand each (6 .. 11): a last band of one
+  // or two row tiles would share its B panels among that few tiles only.
+  const int nbands = max(1, (mt_g + kBand / 2) / kBand);
+  const int bh = mt_g / nbands, tall = mt_g % nbands;  // the first `tall` bands hold bh + 1 row tiles
+  const int tall_tiles = tall * (bh + 1) * n_nt;
+  int band, bsz, rem;
+  if (L < tall_tiles) {
+    bsz = bh + 1;
+    band = L / (bsz * n_nt);
+    rem = L - band * bsz * n_nt;
+  } else {
+    bsz = bh;
+    const int l2 = L - tall_tiles;
+    band = tall + l2 / (bsz * n_nt);
+    rem = l2 - (band - tall) * bsz * n_nt;
+  }
   t.nt = rem / bsz;
-  t.mt = band * kBand + rem % bsz;
+  t.mt = band * bh + min(band, tall) + rem % bsz;
   t.e = g % p.n_experts;
   t.set = g / p.n_experts;
   t.r0 = p.offsets[t.e];
