@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_mi355x.so")
-SOURCES = ["api.hip", "route.hip", "order.hip", "expert_ffn.hip", "gemm_plain.hip", "gemm_mfma.hip", "schedule.hip"]
+SOURCES = ["api.hip", "route.hip", "gate_mfma.hip", "order.hip", "expert_ffn.hip", "gemm_plain.hip", "gemm_mfma.hip", "schedule.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

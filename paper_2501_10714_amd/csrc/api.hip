@@ -461,10 +461,11 @@ static moe_status_t layer_bwd_impl(const char* fn, const moe_config_t* cfg, cons
                                  3, s);
     if (st != MOE_OK) return st;
   }
-  st = launch_dispatch_bwd(*cfg, dxe, row_of, dy, dx, s);
-  if (st != MOE_OK || routed) return st;
-  return launch_route_bwd(*cfg, x, w_gate, (const float*)at(MOE_SAVED_PROBS), (const int32_t*)at(MOE_SAVED_TOPK_IDX),
-                          (const int32_t*)at(MOE_SAVED_POS), dtw, dw_gate, db_gate, dx, w + bp.off_route, s);
+  if (routed) return launch_dispatch_bwd(*cfg, dxe, row_of, dy, dx, s);
+  // backward of the ordering function and of the gate; dx is written once when the gate's share can be folded in
+  return launch_dispatch_route_bwd(*cfg, dxe, row_of, dy, x, w_gate, (const float*)at(MOE_SAVED_PROBS),
+                                   (const int32_t*)at(MOE_SAVED_TOPK_IDX), (const int32_t*)at(MOE_SAVED_POS), dtw, dw_gate,
+                                   db_gate, dx, w + bp.off_route, s);
 }
 
 moe_status_t moe_layer_bwd(const moe_config_t* cfg, const void* dy, const void* x, const void* w_gate, const void* w1,

@@ -148,6 +148,19 @@ moe_status_t launch_route_xmoe_bwd(const moe_config_t& c, const void* x, const v
 moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                               const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                               float* db_gate, void* dx, void* ws, hipStream_t s);
+// The same with the backward of the ordering function in between (whole-layer backward): dlogits, then
+// dx = sum_j dxe[row_of] (+ dy) + dlogits.W_g^T in one pass over dx when the shape allows it (else the gather, then the
+// gate's accumulate into dx), then dW_g and db_g.  dx is overwritten.
+moe_status_t launch_dispatch_route_bwd(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* dy,
+                                       const void* x, const void* w_gate, const float* probs, const int32_t* topk_idx,
+                                       const int32_t* pos, const float* dtopk_w, void* dw_gate, float* db_gate, void* dx,
+                                       void* ws, hipStream_t s);
+// gate_mfma.hip: the gate product on the matrix cores (bf16, E <= 64) with top-k, G(I) and the histogram of choices;
+// hist as gate_small_kernel / gate_topk_kernel leave it ([E][top_k][nb]), nb = 64-token tiles
+bool gate_mfma_supported(const moe_config_t& c);
+moe_status_t launch_gate_mfma(const moe_config_t& c, const void* x, const void* w_gate, const float* b_gate,
+                              float* logits, float* probs, int32_t* topk_idx, float* topk_w, int32_t* hist, int nb,
+                              hipStream_t s);
 // order.hip
 moe_status_t launch_dispatch(const moe_config_t& c, const void* x, const int32_t* row_of, void* xe, hipStream_t s);
 // chunked layer (FSMoE Sec. 4.2): row ranges of chunk c of every expert, and the dispatch of one chunk
@@ -157,6 +170,10 @@ moe_status_t launch_dispatch_rows(const moe_config_t& c, const void* x, const in
                                   const int32_t* end, int r, void* xe, hipStream_t s);
 moe_status_t launch_dispatch_bwd(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* dy, void* dx,
                                  hipStream_t s);
+// dispatch backward with the gate's share of dx folded in: dx = sum_j dxe[row_of] (+ dy) + dl . W_g^T (small E only)
+bool dispatch_bwd_gate_supported(const moe_config_t& c);
+moe_status_t launch_dispatch_bwd_gate(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* dy,
+                                      const float* dl, const void* w_gate, void* dx, hipStream_t s);
 moe_status_t launch_combine(const moe_config_t& c, const void* q, const float* topk_w, const int32_t* row_of,
                             const void* x, void* y, hipStream_t s);
 moe_status_t launch_combine_bwd(const moe_config_t& c, const void* dy, const void* q, const float* topk_w,

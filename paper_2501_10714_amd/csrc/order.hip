@@ -124,6 +124,74 @@ __global__ __launch_bounds__(kBlock) void gather_sum_kernel(const T* __restrict_
   }
 }
 
+// Backward of the ordering function with the gate's share of dx folded in (FSMoE Sec. 4.4):
+//   dx[t,:] = sum_j dxe[row_of[t,j], :] (+ dy[t,:]) + dlogits[t,:] . W_g^T
+// so that dx is written once instead of being written by the gather and read and written again by the gate's backward.
+// A lane owns the same CH 16-byte column chunks for every token it meets and keeps the W_g rows of those columns in
+// registers (CH x V x GE fp32 values, experts past E zero); a workgroup walks token groups in a grid-stride loop.
+template <typename T, int CH, int GE>
+__global__ __launch_bounds__(kBlock) void gather_gate_kernel(const T* __restrict__ src, const int32_t* __restrict__ row_of,
+                                                             const T* __restrict__ res, const float* __restrict__ dl,
+                                                             const T* __restrict__ w_gate, T* __restrict__ out,
+                                                             int n_tokens, int d_model, int n_experts, int top_k, int tpr) {
+  constexpr int V = Elem<T>::kVec;
+  const int rpb = kBlock / tpr;
+  const int lane = threadIdx.x % tpr, sub = threadIdx.x / tpr;
+  const int chunks = d_model / V;
+  float wreg[CH][V][GE];
+#pragma unroll
+  for (int ch = 0; ch < CH; ++ch) {
+    const int c = lane + ch * tpr;
+#pragma unroll
+    for (int i = 0; i < V; ++i)
+#pragma unroll
+      for (int e = 0; e < GE; ++e)
+        wreg[ch][i][e] = (c < chunks && e < n_experts) ? Elem<T>::ld(w_gate + (size_t)(c * V + i) * n_experts + e) : 0.0f;
+  }
+  const int groups = (n_tokens + rpb - 1) / rpb;
+  for (int tb = blockIdx.x; tb < groups; tb += gridDim.x) {
+    const int t = tb * rpb + sub;
+    if (t >= n_tokens) continue;
+    int rows[kMaxK];
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j) rows[j] = j < top_k ? row_of[(size_t)t * top_k + j] : -1;
+    float dlv[GE];
+#pragma unroll
+    for (int e = 0; e < GE; ++e) dlv[e] = e < n_experts ? dl[(size_t)t * n_experts + e] : 0.0f;
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+      const int c = lane + ch * tpr;
+      if (c >= chunks) break;
+      float acc[V];
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+#pragma unroll
+      for (int j = 0; j < kMaxK; ++j) {
+        if (rows[j] >= 0) {
+          Vec16<T> v;
+          v.load_nt(src + (size_t)rows[j] * d_model + c * V);
+#pragma unroll
+          for (int i = 0; i < V; ++i) acc[i] += v.v[i];
+        }
+      }
+      if (res != nullptr) {
+        Vec16<T> r;
+        r.load_nt(res + (size_t)t * d_model + c * V);
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] += r.v[i];
+      }
+#pragma unroll
+      for (int e = 0; e < GE; ++e)
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = fmaf(dlv[e], wreg[ch][i][e], acc[i]);
+      Vec16<T> o;
+#pragma unroll
+      for (int i = 0; i < V; ++i) o.v[i] = acc[i];
+      o.store(out + (size_t)t * d_model + c * V);
+    }
+  }
+}
+
 // dq[row_of[t,j], :] = w[t,j] * dy[t, :];  dtopk_w[t,j] = <dy[t,:], q[row_of[t,j],:]>
 template <typename T>
 __global__ __launch_bounds__(kBlock) void combine_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ q,
@@ -261,6 +329,55 @@ moe_status_t launch_dispatch_bwd(const moe_config_t& c, const void* dxe, const i
   const void* res = c.add_residual ? dy : nullptr;
   return c.dtype == MOE_BF16 ? gather_t<bf16_t, false>(c, dxe, nullptr, row_of, res, dx, s)
                              : gather_t<float, false>(c, dxe, nullptr, row_of, res, dx, s);
+}
+
+// The fused form needs the W_g rows of a lane's chunks in registers: CH chunks per lane x GE experts <= 16.
+namespace {
+struct GateFold { int ch, ge; };
+bool gate_fold_plan(const moe_config_t& c, GateFold* g) {
+  const RowMap m = row_map(c.d_model / (c.dtype == MOE_BF16 ? 8 : 4));
+  const int chunks = c.d_model / (c.dtype == MOE_BF16 ? 8 : 4);
+  const int ch = ceil_div(chunks, m.tpr);
+  const int ge = c.n_experts <= 8 ? 8 : 16;
+  if (c.n_experts > 16 || ch > 2 || ch * ge > 16) return false;
+  g->ch = ch; g->ge = ge;
+  return true;
+}
+template <typename T, int CH, int GE>
+moe_status_t gather_gate_t(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* res, const float* dl,
+                           const void* w_gate, void* dx, hipStream_t s) {
+  const RowMap m = row_map(c.d_model / Elem<T>::kVec);
+  const int groups = ceil_div(c.n_tokens, m.rpb);
+  const int grid = groups < 1024 ? groups : 1024;  // four workgroups per compute unit walk the token groups
+  hipLaunchKernelGGL((gather_gate_kernel<T, CH, GE>), dim3(grid), dim3(kBlock), 0, s, (const T*)dxe, row_of, (const T*)res,
+                     dl, (const T*)w_gate, (T*)dx, c.n_tokens, c.d_model, c.n_experts, c.top_k, m.tpr);
+  MOE_CHECK_LAUNCH();
+  return MOE_OK;
+}
+}  // namespace
+
+bool dispatch_bwd_gate_supported(const moe_config_t& c) {
+  GateFold g;
+  return gate_fold_plan(c, &g);
+}
+
+moe_status_t launch_dispatch_bwd_gate(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* dy,
+                                      const float* dl, const void* w_gate, void* dx, hipStream_t s) {
+  GateFold g;
+  if (!gate_fold_plan(c, &g)) {
+    set_error("dispatch backward with the gate folded in: shape not supported");
+    return MOE_ERR_UNSUPPORTED;
+  }
+  const void* res = c.add_residual ? dy : nullptr;
+  const bool bf = c.dtype == MOE_BF16;
+  if (g.ch == 1 && g.ge == 8)
+    return bf ? gather_gate_t<bf16_t, 1, 8>(c, dxe, row_of, res, dl, w_gate, dx, s)
+              : gather_gate_t<float, 1, 8>(c, dxe, row_of, res, dl, w_gate, dx, s);
+  if (g.ch == 1)
+    return bf ? gather_gate_t<bf16_t, 1, 16>(c, dxe, row_of, res, dl, w_gate, dx, s)
+              : gather_gate_t<float, 1, 16>(c, dxe, row_of, res, dl, w_gate, dx, s);
+  return bf ? gather_gate_t<bf16_t, 2, 8>(c, dxe, row_of, res, dl, w_gate, dx, s)
+            : gather_gate_t<float, 2, 8>(c, dxe, row_of, res, dl, w_gate, dx, s);
 }
 
 moe_status_t launch_combine(const moe_config_t& c, const void* q, const float* topk_w, const int32_t* row_of,

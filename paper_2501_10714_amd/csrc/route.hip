@@ -18,6 +18,7 @@
 
 #include <atomic>
 #include <mutex>
+#include <type_traits>
 
 #include "common.h"
 #include "gemm_params.h"
@@ -637,7 +638,12 @@ moe_status_t route_t(const moe_config_t& c, const void* x, const void* w_gate, c
   constexpr bool force_wide = false;
 #endif
   const size_t small_lds = small_gate_lds_bytes(c.d_model, c.n_experts, c.top_k, SmallGate<T>::kV);
-  if (mode != kGateFromLogits && small_lds <= (size_t)160 * 1024 && !force_wide) {
+  // bf16, up to 64 experts, the plain gate: the product on the matrix cores, exact fp64 logits only for the tokens
+  // whose top-k decision is close (gate_mfma.hip).  The other modes need every logit exact and take the kernels below.
+  if (std::is_same<T, bf16_t>::value && mode == kGateFull && noise == nullptr && !force_wide && gate_mfma_supported(c)) {
+    const moe_status_t mst = launch_gate_mfma(c, x, w_gate, b_gate, logits, probs, topk_idx, topk_w, hist, p.nb, s);
+    if (mst != MOE_OK) return mst;
+  } else if (mode != kGateFromLogits && small_lds <= (size_t)160 * 1024 && !force_wide) {
     static std::atomic<uint64_t> attr_done{0};
     const moe_status_t ast = allow_full_lds(gate_small_kernel<T>, attr_done);
     if (ast != MOE_OK) return ast;
@@ -677,6 +683,9 @@ constexpr int kDxTokens = 16;    // tokens per block of the dx update
 constexpr int kEc = 8;           // experts per register chunk
 
 constexpr int kSplitTokens = 512;  // tokens per split-K group of the bf16 dW_g product
+
+// steps of the gate's backward: dlogits (and the padded bf16 copies of the MFMA path); dx += dlogits.W_g^T; dW_g and db_g
+enum RouteBwdParts { kPartDl = 1, kPartDx = 2, kPartDw = 4, kPartAll = 7 };
 
 // bf16: the two products of the gate backward go through the MFMA grouped GEMM (fp32: plain kernels)
 inline bool gate_bwd_on_mfma(const moe_config_t& c) { return c.dtype == MOE_BF16; }
@@ -928,7 +937,7 @@ template <typename T>
 moe_status_t route_bwd_plain(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                              const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                              float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
-                             const float* dl_ext, hipStream_t s) {
+                             const float* dl_ext, int parts, hipStream_t s) {
   constexpr int V = Elem<T>::kVec;
   RouteBwdPlan p = route_bwd_plan(c);
   unsigned char* w = static_cast<unsigned char*>(ws);
@@ -937,16 +946,21 @@ moe_status_t route_bwd_plain(const moe_config_t& c, const void* x, const void* w
   float* bpart = reinterpret_cast<float*>(w + p.off_bpart);
   if (dl_ext == nullptr) {
     float* dl_own = reinterpret_cast<float*>(w + p.off_dl);
-    const size_t ne = (size_t)c.n_tokens * c.n_experts;
-    hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
-                       dl_own, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0, c.renormalize, noise, noise_logits);
-    MOE_CHECK_LAUNCH();
+    if (parts & kPartDl) {
+      const size_t ne = (size_t)c.n_tokens * c.n_experts;
+      hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
+                         dl_own, (bf16_t*)nullptr, c.n_tokens, c.n_experts, c.top_k, 0, c.renormalize, noise, noise_logits);
+      MOE_CHECK_LAUNCH();
+    }
     dl = dl_own;
   }
-  hipLaunchKernelGGL(gate_dx_kernel<T>, dim3(ceil_div(c.n_tokens, kDxTokens), ceil_div(c.d_model, 256 * V)), dim3(256),
-                     (size_t)kDxTokens * c.n_experts * sizeof(float), s, dl, (const T*)w_gate, (T*)dx, c.n_tokens,
-                     c.d_model, c.n_experts);
-  MOE_CHECK_LAUNCH();
+  if (parts & kPartDx) {
+    hipLaunchKernelGGL(gate_dx_kernel<T>, dim3(ceil_div(c.n_tokens, kDxTokens), ceil_div(c.d_model, 256 * V)), dim3(256),
+                       (size_t)kDxTokens * c.n_experts * sizeof(float), s, dl, (const T*)w_gate, (T*)dx, c.n_tokens,
+                       c.d_model, c.n_experts);
+    MOE_CHECK_LAUNCH();
+  }
+  if (!(parts & kPartDw)) return MOE_OK;
   hipLaunchKernelGGL(gate_dw_partial_kernel<T>,
                      dim3(p.ntile, ceil_div(c.d_model, kDwThreads * V), ceil_div(c.n_experts, kEc)), dim3(kDwThreads), 0,
                      s, (const T*)x, dl, part, c.n_tokens, c.d_model, c.n_experts);
@@ -970,7 +984,7 @@ moe_status_t route_bwd_plain(const moe_config_t& c, const void* x, const void* w
 moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                             const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                             float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
-                            const float* dl_ext, hipStream_t s) {
+                            const float* dl_ext, int parts, hipStream_t s) {
   RouteBwdPlan p = route_bwd_plan(c);
   unsigned char* w = static_cast<unsigned char*>(ws);
   const float* dl = dl_ext;
@@ -980,21 +994,23 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
   bf16_t* wgp = reinterpret_cast<bf16_t*>(w + p.off_wgp);
   int32_t* tok = reinterpret_cast<int32_t*>(w + p.off_tok);
   const size_t ne = (size_t)c.n_tokens * p.ep;
-  if (dl_ext == nullptr) {
-    float* dl_own = reinterpret_cast<float*>(w + p.off_dl);
-    hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
-                       dl_own, dlb, c.n_tokens, c.n_experts, c.top_k, p.ep, c.renormalize, noise, noise_logits);
-    dl = dl_own;
-  } else {
-    hipLaunchKernelGGL(pad_dl_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, dl_ext, dlb, c.n_tokens,
-                       c.n_experts, p.ep);
+  if (dl_ext == nullptr) dl = reinterpret_cast<float*>(w + p.off_dl);
+  if (parts & kPartDl) {
+    if (dl_ext == nullptr) {
+      hipLaunchKernelGGL(dlogits_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, probs, topk_idx, pos, dtopk_w,
+                         reinterpret_cast<float*>(w + p.off_dl), dlb, c.n_tokens, c.n_experts, c.top_k, p.ep, c.renormalize,
+                         noise, noise_logits);
+    } else {
+      hipLaunchKernelGGL(pad_dl_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, s, dl_ext, dlb, c.n_tokens,
+                         c.n_experts, p.ep);
+    }
+    MOE_CHECK_LAUNCH();
+    const int npad = c.d_model * p.ep > p.nsplit + 1 ? c.d_model * p.ep : p.nsplit + 1;
+    hipLaunchKernelGGL(pad_gate_kernel, dim3(ceil_div(npad, 256)), dim3(256), 0, s, (const bf16_t*)w_gate, wgp, tok,
+                       c.d_model, c.n_experts, p.ep, c.n_tokens, p.nsplit);
+    MOE_CHECK_LAUNCH();
   }
-  MOE_CHECK_LAUNCH();
-  const int npad = c.d_model * p.ep > p.nsplit + 1 ? c.d_model * p.ep : p.nsplit + 1;
-  hipLaunchKernelGGL(pad_gate_kernel, dim3(ceil_div(npad, 256)), dim3(256), 0, s, (const bf16_t*)w_gate, wgp, tok,
-                     c.d_model, c.n_experts, p.ep, c.n_tokens, p.nsplit);
-  MOE_CHECK_LAUNCH();
-  {  // dx += dlb.wgp^T : [N,ep] x [ep,M], B(k=e, n=m) = wgp[m][e]
+  if (parts & kPartDx) {  // dx += dlb.wgp^T : [N,ep] x [ep,M], B(k=e, n=m) = wgp[m][e]
     GemmP g = {};
     g.offsets = tok + p.nsplit + 1; g.row_end = g.offsets + 1; g.n_experts = 1; g.n_pairs = 1;
     g.A[0] = dlb; g.sAi = p.ep; g.sAk = 1;
@@ -1004,6 +1020,7 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
     moe_status_t st = launch_gemm_mfma(g, EPI_ACCUM, false, s);
     if (st != MOE_OK) return st;
   }
+  if (!(parts & kPartDw)) return MOE_OK;
   {  // part[g] = x_g^T.dlb_g : [M,rows] x [rows,ep] for every 512-token group
     GemmP g = {};
     g.offsets = tok; g.row_end = g.offsets + 1; g.n_experts = p.nsplit; g.n_pairs = 1;
@@ -1027,18 +1044,21 @@ moe_status_t route_bwd_bf16(const moe_config_t& c, const void* x, const void* w_
   return MOE_OK;
 }
 
-// the gate's products for dl (own: from probs / dtopk_w; or dl_ext), by dtype and expert count
+// the gate's products for dl (own: from probs / dtopk_w; or dl_ext), by dtype and expert count.
+// parts: which steps run (all by default); the whole-layer backward runs kPartDl, then the backward of the ordering
+// function with the dx product folded in, then kPartDw.
 moe_status_t route_bwd_any(const moe_config_t& c, const void* x, const void* w_gate, const float* probs,
                            const int32_t* topk_idx, const int32_t* pos, const float* dtopk_w, void* dw_gate,
                            float* db_gate, void* dx, void* ws, const float* noise, const float* noise_logits,
-                           const float* dl_ext, hipStream_t s) {
+                           const float* dl_ext, hipStream_t s, int parts = kPartAll) {
   if (gate_bwd_on_mfma(c))
-    return route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, noise, noise_logits, dl_ext, s);
+    return route_bwd_bf16(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, noise, noise_logits, dl_ext,
+                          parts, s);
   if (c.dtype == MOE_BF16)
     return route_bwd_plain<bf16_t>(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, noise,
-                                   noise_logits, dl_ext, s);
+                                   noise_logits, dl_ext, parts, s);
   return route_bwd_plain<float>(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, noise, noise_logits,
-                                dl_ext, s);
+                                dl_ext, parts, s);
 }
 
 // ----------------------------------------------------------------------------- expert choice (Sec. 2.1)
@@ -1484,6 +1504,25 @@ moe_status_t launch_route_bwd(const moe_config_t& c, const void* x, const void* 
     dl_ext = dl;
   }
   return route_bwd_any(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, dl_ext, s);
+}
+
+moe_status_t launch_dispatch_route_bwd(const moe_config_t& c, const void* dxe, const int32_t* row_of, const void* dy,
+                                       const void* x, const void* w_gate, const float* probs, const int32_t* topk_idx,
+                                       const int32_t* pos, const float* dtopk_w, void* dw_gate, float* db_gate, void* dx,
+                                       void* ws, hipStream_t s) {
+  if (c.renormalize == MOE_GATE_EXPERT_CHOICE || !dispatch_bwd_gate_supported(c)) {
+    moe_status_t st = launch_dispatch_bwd(c, dxe, row_of, dy, dx, s);
+    if (st != MOE_OK) return st;
+    return launch_route_bwd(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, s);
+  }
+  moe_status_t st = route_bwd_any(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr,
+                                  nullptr, s, kPartDl);
+  if (st != MOE_OK) return st;
+  const float* dl = reinterpret_cast<const float*>(static_cast<unsigned char*>(ws) + route_bwd_plan(c).off_dl);
+  st = launch_dispatch_bwd_gate(c, dxe, row_of, dy, dl, w_gate, dx, s);
+  if (st != MOE_OK) return st;
+  return route_bwd_any(c, x, w_gate, probs, topk_idx, pos, dtopk_w, dw_gate, db_gate, dx, ws, nullptr, nullptr, nullptr, s,
+                       kPartDw);
 }
 
 // Backward of the noisy gate: the ordinary gate backward for W_g (dH = dlogits), then the same products for

@@ -79,6 +79,33 @@ def check(got, want, tol, name=""):
     return r, n
 
 
+def gate_logits_are_exact(w):
+    """Which gate kernel a workload takes: fp32 inputs, more than 64 experts and expert choice go through the fp64
+    product (every logit is the fp32 rounding of an fp64 sum, bit-equal to the oracle's); bf16 with up to 64 experts
+    goes through the matrix cores with exact logits only for the tokens whose top-k decision is close."""
+    return w.dtype != S.DT_BF16 or w.E > 64 or w.renormalize == 3
+
+
+def check_logits(got, want, w, x64, wg64):
+    """Gate logits against the oracle's.  Exact path: bit-equal.  Matrix-core path: every logit within an eighth of
+    the bound the kernel's decision rule relies on, eps[t,e] = 2^-17 |x_t|_2 |w_e|_2 (it assumes every addition inside
+    a chain of 64 products rounds, doubled), plus one fp32 rounding: the margin is the evidence that the assumed bound
+    on the matrix cores' internal rounding holds with room to spare."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    if gate_logits_are_exact(w):
+        assert np.array_equal(got, want), f"{np.count_nonzero(got != want)} logits differ in bits"
+        return
+    eps = 2.0 ** -17 * np.sqrt((x64 * x64).sum(1))[:, None] * np.sqrt((wg64 * wg64).sum(0))[None, :]
+    d = np.abs(got - want)
+    bound = eps / 8 + 2.0 ** -23 * np.abs(want)
+    bad = np.nonzero(~(d <= bound))
+    assert bad[0].size == 0, (f"{bad[0].size} logits outside eps/8; worst ratio {np.nanmax(d / bound):.3g} "
+                              f"at {bad[0][:3]}, {bad[1][:3]}")
+    scale = float(np.max(np.abs(want)))
+    assert float(d.max()) <= 1e-5 * scale, "logits differ by more than 1e-5 of the largest"
+
+
 def cap_of(w):
     """Capacity of a workload: the product's moe_capacity, which must agree with the oracle's formula."""
     cap = capacity_of(w)

@@ -59,8 +59,16 @@ def test_routed_layer_is_bit_identical_to_the_fused_layer(name, r):
         got = moe.saved_view(cfg, b.saved, n, dt)[:A * width]
         want = moe.saved_view(cfg, ref.saved, n, dt)[:A * width]
         assert same_bits(got, want), n
-    for n in ("y", "dx", "dw1", "dw2", "dw_gate") + (("dw3",) if w.gated else ()) + (("db_gate",) if has_bias else ()):
+    for n in ("y", "dw1", "dw2", "dw_gate") + (("dw3",) if w.gated else ()) + (("db_gate",) if has_bias else ()):
         assert same_bits(getattr(b, n), getattr(ref, n)), n
+    # dx: the whole-layer call adds the gate's share inside the backward of the ordering function, from fp32 dlogits, and
+    # rounds dx once (shapes with up to 16 experts); the stage calls round the experts' share, then moe_route_bwd adds
+    # to it (bf16: through the matrix cores, with dlogits rounded to bf16) and rounds again.  Both are within the dtype's
+    # tolerance of the oracle; here they are held to that tolerance against each other.
+    if same_bits(b.dx, ref.dx):
+        return
+    assert w.E <= 16 and w.renormalize != 3, "dx differs although the gate's share was not folded in"
+    check(to_np(b.dx), to_np(ref.dx), TOL[w.dtype], "dx")
 
 
 @pytest.mark.parametrize("name,r", [("xmoe_bf16_topk", 1), ("xmoe_bf16_drops", 3), ("xmoe_f32_sigmoid", 2)])
