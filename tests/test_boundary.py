@@ -145,3 +145,19 @@ def test_the_product_path_never_reaches_the_oracle():
     top = [n for n in tree.body if isinstance(n, (ast.Import, ast.ImportFrom))]
     assert all("oracle" not in (getattr(n, "module", None) or " ".join(a.name for a in n.names)) for n in top)
     assert "moe_harness" not in open(os.path.join(ROOT, "bench.py")).read()
+
+
+def test_bench_traffic_constant_is_the_profile_total():
+    """roofline.traffic of bench.py is a constant taken from the rocprofv3 byte-counter summary under profiles/: the two
+    must say the same (read + written GB per step of the six expert-GEMM launches at the Mixtral shape)."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    text = open(os.path.join(ROOT, "profiles", "gg_mfma_kernel_mixtral_hbm_traffic.md")).read()
+    m = re.search(r"Per step \(six launches\): ([0-9.]+) GB read \+ ([0-9.]+) GB written = ([0-9.]+) GB", text)
+    assert m, "summary line not found in the profile"
+    read_gb, written_gb, total_gb = map(float, m.groups())
+    t = bench.MEASURED_GEMM_TRAFFIC["mixtral"]
+    assert abs(t["read"] / 1e9 - read_gb) < 0.05 and abs(t["written"] / 1e9 - written_gb) < 0.05
+    assert abs((t["read"] + t["written"]) / 1e9 - total_gb) < 0.1
