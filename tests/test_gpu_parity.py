@@ -61,9 +61,10 @@ CASES = {
 
 # One combination stays off the GPU: the expert FFN calls at the shape "gate_48_experts" (48 experts of 0 .. 65 rows,
 # M = 320, H = 64, SwiGLU) ended a run with a GPU memory fault whose cause reading the grouped-GEMM kernels has not
-# shown (every address computed for this shape stays inside its tensor; each feature of the shape is covered by a
-# case that passes).  Until the cause is known the case runs the gate, ordering and gate-backward tests only.
-FFN_SKIP = {"gate_48_experts": "expert FFN at this shape ended in a GPU memory fault; cause not yet shown, see DESIGN.md"}
+# shown (every address computed for this shape stays inside its tensor, also in the host model of the addressing that
+# tests/test_gemm_address_model.py runs on this shape; each feature of the shape is covered by a case that passes).
+# Until the cause is known the case runs the gate, ordering and gate-backward tests only.
+FFN_SKIP = {"gate_48_experts": "expert FFN at this shape ended in a GPU memory fault; cause not yet shown (a host model of the kernels' addressing, tests/test_gemm_address_model.py, finds every access in bounds)"}
 
 
 def ffn_cases():
