@@ -95,8 +95,14 @@ int32_t moe_capacity(int32_t n_tokens, int32_t n_experts, int32_t top_k, double 
 moe_status_t moe_workspace_bytes(const moe_config_t* cfg, size_t* workspace_bytes, size_t* saved_bytes);
 
 /* Gate + capacity (Sec. 2.1 "Gating Function" and the capacity rule of the ordering function).
- *   logits[t,e] = fp32( sum_m x[t,m] * w_gate[m,e] + b_gate[e] ), the sum carried in fp64
- *   topk_idx[t,j] = expert with the j-th largest logit (ties: lower index), j = 0 is the largest
+ *   logits[t,e] = sum_m x[t,m] * w_gate[m,e] + b_gate[e], returned as fp32.
+ *                 fp32 inputs, more than 64 experts, expert choice: the sum is carried in fp64 and rounded once.
+ *                 bf16 inputs, up to 64 experts: the (exact) products are summed on the matrix cores in fp32 chains
+ *                 of 64 and the chains in fp64; such a logit lies within 2^-17 * |x[t,:]|_2 * |w_gate[:,e]|_2 of the
+ *                 exact sum (in practice 1e-7 .. 1e-6 of the largest logit), and every logit that a top-k decision
+ *                 depends on within that bound is recomputed as the fp64 sum.
+ *   topk_idx[t,j] = expert with the j-th largest logit (ties: lower index), j = 0 is the largest; in both cases the
+ *                 decision is the one the fp64 sums, rounded once to fp32, give
  *   probs = G(I): renormalize=1 -> softmax over the k kept logits, exactly 0 elsewhere;
  *                 renormalize=0 -> softmax over all E; renormalize=2 -> sigma(logits), all E
  *   topk_w[t,j] = probs[t, topk_idx[t,j]]
