@@ -1,19 +1,26 @@
 // Gate, top-k, capacity positions (FSMoE Sec. 2.1 "Gating Function" and the capacity rule of the
 // ordering function) and the gate's backward pass (Sec. 4.4).
 //
-// Forward, four launches on one stream:
-//   1. widen_gate_kernel   W_g -> fp64, zero padded to [Mpad][EP]          (tiny)
-//   2. gate_topk_kernel    logits (fp64 accumulate, one rounding to fp32), top-k, G(I), and a
-//                          histogram of choices per (expert, rank j, 64-token tile)
-//   3. scan_hist_kernel    exclusive prefix over (j, tile) for every expert: the number of earlier
+// Forward, up to four launches on one stream:
+//   1. the gate: logits, top-k, G(I), and a histogram of choices per (expert, rank j, 64-token tile).  Three kernels,
+//      chosen by shape (route_t):
+//        gate_mfma_kernel (gate_mfma.hip)  bf16 inputs, up to 64 experts, the plain gate: product on the matrix cores,
+//                          fp64 repair of the logits a close top-k decision rests on;
+//        gate_small_kernel  everything else whose W_g rows of one 8-expert group fit in LDS: fp64 product on the
+//                          vector ALU with the token rows in registers, every logit rounded once to fp32;
+//        widen_gate_kernel + gate_topk_kernel  very large d_model (W_g widened to fp64, both operands staged through
+//                          LDS in K chunks); gate_topk_kernel also runs the tail alone for gates that bring their
+//                          own logits (X-MoE) and the product alone (the noise product of the noisy gate);
+//   2. scan_hist_kernel    exclusive prefix over (j, tile) for every expert: the number of earlier
 //                          assignments to that expert in rank-major, token-minor order
-//   4. positions_kernel    count = min(total, T), offsets = exclusive prefix of count, then
+//   3. positions_kernel    count = min(total, T), offsets = exclusive prefix of count, then
 //                          pos / row_of / src_of_row: tile base + rank among the wave's lanes
 // Positions come from prefix sums only (no atomics decide an index), so the result is the same on
 // every run and equals the serial walk "for j, for t".
 //
-// The logits are an fp64 GEMM on the vector ALU (register tiled, operands through LDS): the price of
-// routing that matches an independent oracle bit for bit whatever the summation order.
+// In the two fp64 gate kernels the logits are an fp64 product on the vector ALU: routing and logits that match an
+// independent fp64 evaluation bit for bit whatever the summation order, at the price of being bound by that unit.
+// The matrix-core gate keeps the routing at that bar and gives up bit-equality of the logits no decision rests on.
 #include <stdlib.h>
 
 #include <atomic>
