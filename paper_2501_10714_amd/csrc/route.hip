@@ -223,8 +223,6 @@ __global__ __launch_bounds__(kGateThreads) void gate_topk_kernel(
   double* red = xs + R * EE * kTile;    // [EE][kTile]
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
   const int tg = tid & 7, eg = (tid >> 3) % NEG, ks = tid / (8 * NEG);
   const int t0 = blockIdx.x * kTile;
   const int lgs = n_experts + 1;
